@@ -1,0 +1,736 @@
+// HIP kernels of the verify pass for gfx950 (CDNA4, 64-wide waves).
+//
+// One pass = k <= 16 token rows through a Llama-style decoder against the
+// key-value cache (VerifyTokens of Algorithm 1), greedy arg-max per row, and
+// the longest-matching-prefix test.  The pass is bound by streaming the
+// weights once from HBM, so the design is about keeping many 16-byte loads in
+// flight and reading every weight byte exactly once:
+//   * weights are stored in matrix-core operand order: a wave's load of one
+//     16x32 (bf16) / 16x16 (fp32) weight fragment is 1 KiB contiguous;
+//   * the k rows are padded to the 16-row MFMA tile, so a row's result does
+//     not depend on k: a k-row pass equals k one-row passes bit for bit;
+//   * a workgroup owns whole 16-column output tiles; its 8 waves split the
+//     contraction dimension and reduce through LDS in a fixed order (no float
+//     atomics anywhere), then run the fused epilogue (RMSNorm scale, rotary
+//     embedding + cache append, SwiGLU, residual, arg-max partials);
+//   * activations travel between stages as bf16 hi+lo pairs (x = hi + lo to
+//     ~16 mantissa bits), so the bf16 MFMA path loses nothing on the
+//     activation side; weights are exact bf16.
+// Every stage is a __device__ function over (workgroup id, workgroup count) so
+// the same code runs as one kernel per stage or inside one persistent kernel.
+#include "amusd_launch.h"
+
+namespace amusd {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+// ---------------------------------------------------------------- dtype traits
+struct BF16 {
+    static constexpr int EPL = 8;         // elements in a lane's 16-byte fragment
+    static constexpr int KB = 32;         // contraction elements per fragment (4 lane groups x EPL)
+    static constexpr int ESZ = 2;
+    static constexpr int TPB = 2;         // 16-key score tiles per value block
+    static constexpr int BLOCK_KEYS = 32;
+    static constexpr bool HAS_LO = true;
+    static __device__ __forceinline__ v4f mfma(uint4 a, uint4 b, v4f c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+    }
+};
+struct FP32 {
+    static constexpr int EPL = 4;
+    static constexpr int KB = 16;
+    static constexpr int ESZ = 4;
+    static constexpr int TPB = 1;
+    static constexpr int BLOCK_KEYS = 16;
+    static constexpr bool HAS_LO = false;
+    static __device__ __forceinline__ v4f mfma(uint4 a, uint4 b, v4f c) {
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+        return c;
+    }
+};
+
+__device__ __forceinline__ uint32_t bf16_rne(float x) {
+    uint32_t u = __float_as_uint(x);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// store x into an activation buffer: fp32 as is; bf16 as hi + lo
+template <class DT>
+__device__ __forceinline__ void store_act(void* hi, void* lo, size_t idx, float x) {
+    if constexpr (DT::HAS_LO) {
+        uint32_t h = bf16_rne(x);
+        uint32_t l = bf16_rne(x - bf16_to_f32(h));
+        reinterpret_cast<uint16_t*>(hi)[idx] = (uint16_t)h;
+        reinterpret_cast<uint16_t*>(lo)[idx] = (uint16_t)l;
+    } else {
+        reinterpret_cast<float*>(hi)[idx] = x;
+    }
+}
+
+template <class DT>
+__device__ __forceinline__ uint4 load_frag(const void* base, size_t elem_index) {
+    return *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(base) + elem_index * DT::ESZ);
+}
+
+__device__ __forceinline__ float wave_xor_add(float v, int off) { return v + __shfl_xor(v, off, 64); }
+
+// ---------------------------------------------------------------- RMS scale of the 16 rows
+// Sums the per-tile partial sums of squares in a fixed order and leaves
+// 1/sqrt(mean + eps) for each row in rstd[16] (LDS).  512 threads.
+__device__ __forceinline__ void compute_rstd(const DevModel& M, float* rstd) {
+    const int tid = threadIdx.x;
+    const int m = tid >> 5, s = tid & 31;
+    const int ntp = M.d / 16;
+    float acc = 0.f;
+    for (int t = s; t < ntp; t += 32) acc += M.ssq[t * kRows + m];
+    acc = wave_xor_add(acc, 16);
+    acc = wave_xor_add(acc, 8);
+    acc = wave_xor_add(acc, 4);
+    acc = wave_xor_add(acc, 2);
+    acc = wave_xor_add(acc, 1);
+    if (s == 0) rstd[m] = 1.0f / sqrtf(acc / (float)M.d + M.eps);
+    __syncthreads();
+}
+
+// ---------------------------------------------------------------- skinny GEMM stage
+// C[n][m] = sum_k W[n][k] * A[m][k] for the 16 rows m, output tiles of 16
+// columns n.  Workgroup wg owns tiles wg, wg+nwg, ...; up to 8 at a time.
+// Wave w contracts over its slice of the K blocks; partial tiles are summed
+// through LDS in wave order, then epi.item() runs on every pair
+// (column r, column r+8) of each tile.
+template <class DT, class Epi>
+__device__ __forceinline__ void gemm_stage(const uint4* __restrict__ W, int n_tiles, int kblocks,
+                                           const void* __restrict__ Ahi, const void* __restrict__ Alo, int lda,
+                                           int k_rows, int wg, int nwg, Epi& epi, float* smem) {
+    constexpr int NT = kMaxTilesPerRound;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 15, g = lane >> 4;
+    const int kb0 = (kblocks * wave) / kWaves, kb1 = (kblocks * (wave + 1)) / kWaves;
+    const int mine = wg < n_tiles ? (n_tiles - wg + nwg - 1) / nwg : 0;
+    const bool row_on = m < k_rows;
+    for (int i0 = 0; i0 < mine; i0 += NT) {
+        const int nt = min(NT, mine - i0);
+        v4f acc[NT];
+        const uint4* wp[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            acc[j] = v4f{0.f, 0.f, 0.f, 0.f};
+            const int t = wg + nwg * (i0 + (j < nt ? j : 0));
+            wp[j] = W + ((size_t)t * kblocks + kb0) * 64 + lane;
+        }
+        const size_t abase = (size_t)m * lda + (size_t)g * DT::EPL;
+#pragma unroll 2
+        for (int kb = kb0; kb < kb1; ++kb) {
+            uint4 bh = uint4{0, 0, 0, 0}, bl = uint4{0, 0, 0, 0};
+            if (row_on) {
+                bh = load_frag<DT>(Ahi, abase + (size_t)kb * DT::KB);
+                if constexpr (DT::HAS_LO) bl = load_frag<DT>(Alo, abase + (size_t)kb * DT::KB);
+            }
+            uint4 a[NT];
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                if (j < nt) a[j] = wp[j][(size_t)(kb - kb0) * 64];
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                if (j < nt) {
+                    acc[j] = DT::mfma(a[j], bh, acc[j]);
+                    if constexpr (DT::HAS_LO) acc[j] = DT::mfma(a[j], bl, acc[j]);
+                }
+        }
+        // partial tiles to LDS as [wave][tile][m][n]; lane holds n = 4g..4g+3 of row m
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+            if (j < nt) *reinterpret_cast<v4f*>(smem + ((wave * NT + j) * 256 + m * 16 + g * 4)) = acc[j];
+        __syncthreads();
+        for (int item = tid; item < NT * 128; item += kThreads) {
+            const int j = item >> 7, mm = (item >> 3) & 15, r = item & 7;
+            const bool valid = j < nt;
+            float v1 = 0.f, v2 = 0.f;
+            if (valid) {
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) {
+                    v1 += smem[(w * NT + j) * 256 + mm * 16 + r];
+                    v2 += smem[(w * NT + j) * 256 + mm * 16 + r + 8];
+                }
+            }
+            epi.item(wg + nwg * (i0 + (valid ? j : 0)), j, mm, r, v1, v2, valid);
+        }
+        __syncthreads();
+        epi.round_end(nt);
+    }
+}
+
+// ---------------------------------------------------------------- epilogues
+// Residual update for a pair of columns, then the next GEMM's input: x*gain
+// split into hi/lo, and the tile's partial sum of squares per row.
+template <class DT>
+__device__ __forceinline__ void residual_pair(const DevModel& M, const float* __restrict__ gain, int tile, int mm, int r,
+                                              float x1, float x2, int k_rows, bool valid) {
+    const int c1 = tile * 16 + r, c2 = c1 + 8;
+    float sq = 0.f;
+    if (valid && mm < k_rows) {
+        const size_t i1 = (size_t)mm * M.d + c1, i2 = (size_t)mm * M.d + c2;
+        M.X[i1] = x1;
+        M.X[i2] = x2;
+        store_act<DT>(M.A_hi, M.A_lo, i1, x1 * gain[c1]);
+        store_act<DT>(M.A_hi, M.A_lo, i2, x2 * gain[c2]);
+        sq = x1 * x1 + x2 * x2;
+    }
+    sq = wave_xor_add(sq, 1);
+    sq = wave_xor_add(sq, 2);
+    sq = wave_xor_add(sq, 4);
+    if (valid && r == 0) M.ssq[tile * kRows + mm] = sq;
+}
+
+template <class DT>
+struct EpiResidual {   // O-projection and down-projection: X += C, feed the next norm
+    const DevModel& M;
+    const float* gain_next;
+    int k_rows;
+    __device__ __forceinline__ void item(int tile, int /*slot*/, int mm, int r, float v1, float v2, bool valid) {
+        float x1 = 0.f, x2 = 0.f;
+        if (valid && mm < k_rows) {
+            x1 = M.X[(size_t)mm * M.d + tile * 16 + r] + v1;
+            x2 = M.X[(size_t)mm * M.d + tile * 16 + r + 8] + v2;
+        }
+        residual_pair<DT>(M, gain_next, tile, mm, r, x1, x2, k_rows, valid);
+    }
+    __device__ __forceinline__ void round_end(int) {}
+};
+
+template <class DT>
+struct EpiQKV {        // RMS scale, rotary embedding on (i, i+hd/2) pairs, Q to its buffer, K/V appended to the cache
+    const DevModel& M;
+    const DevLayer& Ly;
+    const float* rstd;   // LDS
+    int L, k_rows;
+    __device__ __forceinline__ void item(int tile, int /*slot*/, int mm, int r, float v1, float v2, bool valid) {
+        if (!valid || mm >= k_rows) return;
+        const int hd = M.hd, tph = hd / 16;
+        const float sc = rstd[mm];
+        float x1 = v1 * sc, x2 = v2 * sc;
+        const int pos = L + mm;
+        const int qt = M.qdim / 16, kt = M.kvdim / 16;
+        if (tile < qt + kt) {
+            const bool isq = tile < qt;
+            const int tt = isq ? tile : tile - qt;
+            const int head = tt / tph, i = (tt % tph) * 8 + r;
+            const float c = M.rope_cos[(size_t)pos * (hd / 2) + i], s = M.rope_sin[(size_t)pos * (hd / 2) + i];
+            const float y1 = x1 * c - x2 * s, y2 = x1 * s + x2 * c;
+            if (isq) {
+                const size_t o = (size_t)mm * M.qdim + head * hd + i;
+                store_act<DT>(M.Q_hi, M.Q_lo, o, y1);
+                store_act<DT>(M.Q_hi, M.Q_lo, o + hd / 2, y2);
+            } else {
+                const size_t o = ((size_t)head * M.ctx_pad + pos) * hd + i;
+                if constexpr (DT::HAS_LO) {
+                    reinterpret_cast<uint16_t*>(Ly.kcache)[o] = (uint16_t)bf16_rne(y1);
+                    reinterpret_cast<uint16_t*>(Ly.kcache)[o + hd / 2] = (uint16_t)bf16_rne(y2);
+                } else {
+                    reinterpret_cast<float*>(Ly.kcache)[o] = y1;
+                    reinterpret_cast<float*>(Ly.kcache)[o + hd / 2] = y2;
+                }
+            }
+        } else {
+            const int tt = tile - qt - kt;
+            const int head = tt / tph, j = tt % tph;   // value features j*16 + r and j*16 + r + 8
+            constexpr int BK = DT::BLOCK_KEYS;
+            const int b = pos / BK, q = pos % BK;
+            const int e = (q / 16) * 4 + (q % 4), gg = (q % 16) / 4;
+            const size_t blk = ((size_t)head * (M.ctx_pad / BK) + b) * tph + j;
+            const size_t o1 = (blk * 64 + gg * 16 + r) * DT::EPL + e;
+            const size_t o2 = (blk * 64 + gg * 16 + r + 8) * DT::EPL + e;
+            if constexpr (DT::HAS_LO) {
+                reinterpret_cast<uint16_t*>(Ly.vcache)[o1] = (uint16_t)bf16_rne(x1);
+                reinterpret_cast<uint16_t*>(Ly.vcache)[o2] = (uint16_t)bf16_rne(x2);
+            } else {
+                reinterpret_cast<float*>(Ly.vcache)[o1] = x1;
+                reinterpret_cast<float*>(Ly.vcache)[o2] = x2;
+            }
+        }
+    }
+    __device__ __forceinline__ void round_end(int) {}
+};
+
+template <class DT>
+struct EpiSwiGLU {     // tile rows 0-7 are gate features, 8-15 the matching up features
+    const DevModel& M;
+    const float* rstd;
+    int k_rows;
+    __device__ __forceinline__ void item(int tile, int /*slot*/, int mm, int r, float v1, float v2, bool valid) {
+        if (!valid || mm >= k_rows) return;
+        const float sc = rstd[mm];
+        const float gate = v1 * sc, up = v2 * sc;
+        const float h = gate / (1.0f + __expf(-gate)) * up;
+        store_act<DT>(M.H_hi, M.H_lo, (size_t)mm * M.F + tile * 8 + r, h);
+    }
+    __device__ __forceinline__ void round_end(int) {}
+};
+
+// ---------------------------------------------------------------- LDS layout (dynamic shared memory, floats)
+constexpr int kAttPad = 4;    // row padding of the attention partials (spreads LDS banks)
+constexpr int kScratchFloats = kWaves * kRows * (128 + kAttPad) + kWaves * kRows * 2;   // attention partials; >= GEMM reduction area
+static_assert(kScratchFloats >= kWaves * kMaxTilesPerRound * 256, "GEMM reduction area must fit");
+constexpr int kOffRstd = kScratchFloats;
+constexpr int kOffTileBestV = kOffRstd + kRows;
+constexpr int kOffTileBestI = kOffTileBestV + kMaxTilesPerRound * kRows;
+constexpr int kSmemFloats = kOffTileBestI + kMaxTilesPerRound * kRows;
+
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
+
+struct EpiLMHead {     // logits (optionally stored); per-row arg-max over this workgroup's tiles, lowest id on ties
+    const DevModel& M;
+    float* smem;
+    int k_rows, keep;
+    float run_v;         // thread mm < 16 keeps the workgroup's running best for row mm
+    int run_i;
+    __device__ __forceinline__ void item(int tile, int slot, int mm, int r, float v1, float v2, bool valid) {
+        const float sc = smem[kOffRstd + mm];
+        const float z1 = v1 * sc, z2 = v2 * sc;
+        const int c1 = tile * 16 + r, c2 = c1 + 8;
+        const bool on = valid && mm < k_rows;
+        if (on && keep) {
+            M.logits[(size_t)mm * M.V + c1] = z1;
+            M.logits[(size_t)mm * M.V + c2] = z2;
+        }
+        float bv = on ? z1 : -INFINITY;
+        int bi = on ? c1 : 0x7fffffff;
+        if (on && better(z2, c2, bv, bi)) { bv = z2; bi = c2; }
+#pragma unroll
+        for (int off = 1; off < 8; off <<= 1) {     // the 8 lanes of one (tile,row) are adjacent
+            const float ov = __shfl_xor(bv, off, 64);
+            const int oi = __shfl_xor(bi, off, 64);
+            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+        }
+        if (r == 0) {
+            smem[kOffTileBestV + slot * kRows + mm] = bv;
+            reinterpret_cast<int*>(smem)[kOffTileBestI + slot * kRows + mm] = bi;
+        }
+    }
+    __device__ __forceinline__ void round_end(int nt) {   // called after a barrier
+        const int mm = threadIdx.x;
+        if (mm < kRows) {
+            for (int j = 0; j < nt; ++j) {
+                const float v = smem[kOffTileBestV + j * kRows + mm];
+                const int i = reinterpret_cast<const int*>(smem)[kOffTileBestI + j * kRows + mm];
+                if (better(v, i, run_v, run_i)) { run_v = v; run_i = i; }
+            }
+        }
+    }
+};
+
+// ---------------------------------------------------------------- stages
+// Embedding rows -> residual stream, first norm input, sums of squares.
+template <class DT>
+__device__ __forceinline__ void stage_embed(const DevModel& M, int wg, int nwg) {
+    const int k = M.pp->k;
+    const int ntiles = M.d / 16;
+    const float* gain = M.layers[0].g_attn;
+    // 128 items per tile (16 rows x 8 column pairs); 4 tiles per sweep of the 512 threads
+    const int sub = threadIdx.x >> 7, mm = (threadIdx.x >> 3) & 15, r = threadIdx.x & 7;
+    for (int t0 = wg * 4; t0 < ntiles; t0 += nwg * 4) {
+        const int tile = t0 + sub;
+        const bool valid = tile < ntiles;
+        float x1 = 0.f, x2 = 0.f;
+        if (valid && mm < k) {
+            const size_t o = (size_t)M.tokens[mm] * M.d + tile * 16 + r;
+            if constexpr (DT::HAS_LO) {
+                x1 = bf16_to_f32(reinterpret_cast<const uint16_t*>(M.embed)[o]);
+                x2 = bf16_to_f32(reinterpret_cast<const uint16_t*>(M.embed)[o + 8]);
+            } else {
+                x1 = reinterpret_cast<const float*>(M.embed)[o];
+                x2 = reinterpret_cast<const float*>(M.embed)[o + 8];
+            }
+        }
+        residual_pair<DT>(M, gain, valid ? tile : 0, mm, r, x1, x2, k, valid);
+    }
+}
+
+template <class DT>
+__device__ __forceinline__ void stage_qkv(const DevModel& M, int layer, int wg, int nwg, float* smem) {
+    const DevLayer& Ly = M.layers[layer];
+    compute_rstd(M, smem + kOffRstd);
+    EpiQKV<DT> epi{M, Ly, smem + kOffRstd, M.pp->L, M.pp->k};
+    gemm_stage<DT>(Ly.wqkv, M.nqkv / 16, M.d / DT::KB, M.A_hi, M.A_lo, M.d, M.pp->k, wg, nwg, epi, smem);
+}
+
+template <class DT>
+__device__ __forceinline__ void stage_oproj(const DevModel& M, int layer, int wg, int nwg, float* smem) {
+    const DevLayer& Ly = M.layers[layer];
+    EpiResidual<DT> epi{M, Ly.g_mlp, M.pp->k};
+    gemm_stage<DT>(Ly.wo, M.d / 16, M.qdim / DT::KB, M.O_hi, M.O_lo, M.qdim, M.pp->k, wg, nwg, epi, smem);
+}
+
+template <class DT>
+__device__ __forceinline__ void stage_gateup(const DevModel& M, int layer, int wg, int nwg, float* smem) {
+    const DevLayer& Ly = M.layers[layer];
+    compute_rstd(M, smem + kOffRstd);
+    EpiSwiGLU<DT> epi{M, smem + kOffRstd, M.pp->k};
+    gemm_stage<DT>(Ly.wgu, 2 * M.F / 16, M.d / DT::KB, M.A_hi, M.A_lo, M.d, M.pp->k, wg, nwg, epi, smem);
+}
+
+template <class DT>
+__device__ __forceinline__ void stage_down(const DevModel& M, int layer, int wg, int nwg, float* smem) {
+    const DevLayer& Ly = M.layers[layer];
+    const float* gain_next = layer + 1 < M.n_layers ? M.layers[layer + 1].g_attn : M.g_final;
+    EpiResidual<DT> epi{M, gain_next, M.pp->k};
+    gemm_stage<DT>(Ly.wd, M.d / 16, M.F / DT::KB, M.H_hi, M.H_lo, M.F, M.pp->k, wg, nwg, epi, smem);
+}
+
+template <class DT>
+__device__ __forceinline__ void stage_lmhead(const DevModel& M, int wg, int nwg, float* smem) {
+    compute_rstd(M, smem + kOffRstd);
+    EpiLMHead epi{M, smem, M.pp->k, M.pp->keep_logits, -INFINITY, 0x7fffffff};
+    gemm_stage<DT>(M.wlm, M.V / 16, M.d / DT::KB, M.A_hi, M.A_lo, M.d, M.pp->k, wg, nwg, epi, smem);
+    if (threadIdx.x < kRows && wg < M.lm_wgs) {
+        M.best_val[wg * kRows + threadIdx.x] = epi.run_v;
+        M.best_idx[wg * kRows + threadIdx.x] = epi.run_i;
+    }
+}
+
+// Causal grouped-query attention of the k rows against keys 0 .. L+k-1.
+// Work unit = (kv head, chunk of `chunk` consecutive key positions); wave w of
+// the workgroup takes key block w of the chunk (32 keys bf16 / 16 keys fp32),
+// loads its K and V fragments once and reuses them for the G query heads of
+// the group.  Scores are computed transposed (keys x rows) so that the
+// matrix-core result registers are, after the softmax numerator, already the
+// operand of the P.V product: no transposition through LDS.  Chunk and block
+// boundaries sit at fixed absolute positions, so a row's result does not depend
+// on how many rows the pass has or where the pass starts.
+// Output per (unit, head, row): running max, denominator, unnormalised numerator.
+template <class DT, int HD>
+__device__ __forceinline__ void stage_attention(const DevModel& M, int layer, int wg, int nwg, float* smem) {
+    constexpr int FR = HD / 4 / DT::EPL;     // 16-byte fragments per lane along head_dim
+    constexpr int HT = HD / 16;              // 16-wide head_dim tiles
+    constexpr int BK = DT::BLOCK_KEYS, TPB = DT::TPB;
+    const DevLayer& Ly = M.layers[layer];
+    const int L = M.pp->L, k = M.pp->k;
+    const int T = L + k;
+    const int CS = M.chunk;                  // = kWaves * BK
+    const int nchunks = (T + CS - 1) / CS;
+    const int units = M.Hkv * nchunks;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 15, g = lane >> 4;
+    constexpr int HDP = HD + kAttPad;
+    float* partO = smem;                               // [wave][16][HD + pad]
+    float* partML = smem + kWaves * kRows * HDP;       // [wave][16][2]
+    const int nblk = M.ctx_pad / BK;
+    for (int u = wg; u < units; u += nwg) {
+        const int kvh = u / nchunks, c = u % nchunks;
+        const int p0 = c * CS + wave * BK;
+        const bool active = p0 < T;
+        uint4 kf[TPB][FR], vf[HT];
+        if (active) {
+#pragma unroll
+            for (int t = 0; t < TPB; ++t) {
+                const size_t e0 = ((size_t)kvh * M.ctx_pad + p0 + t * 16 + m) * HD + g * (HD / 4);
+#pragma unroll
+                for (int i = 0; i < FR; ++i) kf[t][i] = load_frag<DT>(Ly.kcache, e0 + i * DT::EPL);
+            }
+            const uint4* vb = reinterpret_cast<const uint4*>(Ly.vcache) + (((size_t)kvh * nblk + p0 / BK) * HT) * 64 + lane;
+#pragma unroll
+            for (int j = 0; j < HT; ++j) vf[j] = vb[j * 64];
+        }
+        for (int hq = 0; hq < M.G; ++hq) {
+            const int head = kvh * M.G + hq;
+            float mx = -INFINITY, lsum = 0.f;
+            v4f o[HT];
+#pragma unroll
+            for (int j = 0; j < HT; ++j) o[j] = v4f{0.f, 0.f, 0.f, 0.f};
+            if (active) {
+                uint4 qh[FR], ql[FR];
+#pragma unroll
+                for (int i = 0; i < FR; ++i) { qh[i] = uint4{0, 0, 0, 0}; ql[i] = uint4{0, 0, 0, 0}; }
+                if (m < k) {
+                    const size_t q0 = (size_t)m * M.qdim + head * HD + g * (HD / 4);
+#pragma unroll
+                    for (int i = 0; i < FR; ++i) {
+                        qh[i] = load_frag<DT>(M.Q_hi, q0 + i * DT::EPL);
+                        if constexpr (DT::HAS_LO) ql[i] = load_frag<DT>(M.Q_lo, q0 + i * DT::EPL);
+                    }
+                }
+                float sv[TPB][4];
+#pragma unroll
+                for (int t = 0; t < TPB; ++t) {
+                    v4f s = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int i = 0; i < FR; ++i) {
+                        s = DT::mfma(kf[t][i], qh[i], s);
+                        if constexpr (DT::HAS_LO) s = DT::mfma(kf[t][i], ql[i], s);
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int key = p0 + t * 16 + g * 4 + e;
+                        sv[t][e] = key <= L + m ? s[e] * M.att_scale : -INFINITY;   // causal: row m sees keys 0..L+m
+                        mx = fmaxf(mx, sv[t][e]);
+                    }
+                }
+                mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                const float mref = mx == -INFINITY ? 0.f : mx;
+                float pv[TPB][4];
+#pragma unroll
+                for (int t = 0; t < TPB; ++t)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        pv[t][e] = __expf(sv[t][e] - mref);
+                        lsum += pv[t][e];
+                    }
+                lsum = wave_xor_add(lsum, 16);
+                lsum = wave_xor_add(lsum, 32);
+                uint4 ph, pl = uint4{0, 0, 0, 0};
+                if constexpr (DT::HAS_LO) {
+                    uint32_t h[8], l[8];
+#pragma unroll
+                    for (int t = 0; t < TPB; ++t)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            h[t * 4 + e] = bf16_rne(pv[t][e]);
+                            l[t * 4 + e] = bf16_rne(pv[t][e] - bf16_to_f32(h[t * 4 + e]));
+                        }
+                    ph = uint4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+                    pl = uint4{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+                } else {
+                    ph = uint4{__float_as_uint(pv[0][0]), __float_as_uint(pv[0][1]), __float_as_uint(pv[0][2]), __float_as_uint(pv[0][3])};
+                }
+#pragma unroll
+                for (int j = 0; j < HT; ++j) {
+                    o[j] = DT::mfma(vf[j], ph, o[j]);
+                    if constexpr (DT::HAS_LO) o[j] = DT::mfma(vf[j], pl, o[j]);
+                }
+            }
+            // wave partial to LDS: o[j][e] is head_dim index 16j + 4g + e of row m
+#pragma unroll
+            for (int j = 0; j < HT; ++j)
+                *reinterpret_cast<v4f*>(partO + ((size_t)(wave * kRows + m) * HDP + j * 16 + g * 4)) = o[j];
+            if (g == 0) {
+                partML[(wave * kRows + m) * 2 + 0] = mx;
+                partML[(wave * kRows + m) * 2 + 1] = lsum;
+            }
+            __syncthreads();
+            // merge the 8 wave partials in wave order: thread = (row, slice of head_dim)
+            {
+                constexpr int PER = HD / 32;
+                const int mm = tid >> 5, c0 = (tid & 31) * PER;
+                if (mm < k) {
+                    float Mx = -INFINITY;
+#pragma unroll
+                    for (int w = 0; w < kWaves; ++w) Mx = fmaxf(Mx, partML[(w * kRows + mm) * 2]);
+                    float den = 0.f, num[PER];
+#pragma unroll
+                    for (int x = 0; x < PER; ++x) num[x] = 0.f;
+#pragma unroll
+                    for (int w = 0; w < kWaves; ++w) {
+                        const float mw = partML[(w * kRows + mm) * 2];
+                        const float wt = mw == -INFINITY ? 0.f : __expf(mw - Mx);
+                        den += wt * partML[(w * kRows + mm) * 2 + 1];
+#pragma unroll
+                        for (int x = 0; x < PER; ++x) num[x] += wt * partO[(size_t)(w * kRows + mm) * HDP + c0 + x];
+                    }
+                    float* out = M.att_part + (((size_t)u * M.G + hq) * kRows + mm) * (HD + 2);
+                    if ((tid & 31) == 0) { out[0] = Mx; out[1] = den; }
+#pragma unroll
+                    for (int x = 0; x < PER; ++x) out[2 + c0 + x] = num[x];
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// Merge of the chunk partials of each (head, row) in chunk order -> normalised
+// attention output as the O-projection's input.  One wave per (head, row).
+template <class DT, int HD>
+__device__ __forceinline__ void stage_attn_merge(const DevModel& M, int wg, int nwg) {
+    const int L = M.pp->L, k = M.pp->k;
+    const int T = L + k, CS = M.chunk;
+    const int nchunks = (T + CS - 1) / CS;
+    const int lane = threadIdx.x & 63;
+    const int gw = wg * kWaves + (threadIdx.x >> 6), nw = nwg * kWaves;
+    constexpr int PER = HD / 64;
+    for (int x = gw; x < M.Hq * k; x += nw) {
+        const int head = x / k, mm = x % k;
+        const int kvh = head / M.G, hq = head % M.G;
+        const int nch = (L + mm) / CS + 1;            // chunks holding keys this row can see
+        float Mx = -INFINITY;
+        for (int c = 0; c < nch; ++c)
+            Mx = fmaxf(Mx, M.att_part[((((size_t)kvh * nchunks + c) * M.G + hq) * kRows + mm) * (HD + 2)]);
+        float den = 0.f, num[PER];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) num[i] = 0.f;
+        for (int c = 0; c < nch; ++c) {
+            const float* p = M.att_part + ((((size_t)kvh * nchunks + c) * M.G + hq) * kRows + mm) * (HD + 2);
+            const float mc = p[0];
+            const float wt = mc == -INFINITY ? 0.f : __expf(mc - Mx);
+            den += wt * p[1];
+#pragma unroll
+            for (int i = 0; i < PER; ++i) num[i] += wt * p[2 + lane + 64 * i];
+        }
+        const float inv = 1.0f / den;
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            store_act<DT>(M.O_hi, M.O_lo, (size_t)mm * M.qdim + head * HD + lane + 64 * i, num[i] * inv);
+    }
+}
+
+// Arg-max across workgroups by wave shuffles, then the mismatch test of
+// Algorithm 1: target = [p_ctx, g[0], .., g[k-2]], accept the longest prefix
+// with draft == target, emit the model's own token at the first mismatch (or
+// g[k-1] when all match).  One wave.
+__device__ __forceinline__ void stage_accept(const DevModel& M) {
+    const int lane = threadIdx.x & 63;
+    const int k = M.pp->k;
+    int myg = -1;
+    for (int mm = 0; mm < k; ++mm) {
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+        for (int w = lane; w < M.lm_wgs; w += 64) {
+            const float v = M.best_val[w * kRows + mm];
+            const int i = M.best_idx[w * kRows + mm];
+            if (better(v, i, bv, bi)) { bv = v; bi = i; }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float ov = __shfl_xor(bv, off, 64);
+            const int oi = __shfl_xor(bi, off, 64);
+            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+        }
+        if (lane == mm) myg = bi;
+    }
+    if (lane < kRows) M.res->greedy[lane] = lane < k ? myg : -1;
+    // lane j holds g[j]; target[j] = j ? g[j-1] : p_ctx
+    const int prev = __shfl_up(myg, 1, 64);
+    const int target = lane == 0 ? M.pp->p_ctx : prev;
+    const bool match = lane < k && (M.pp->force_accept || M.tokens[lane] == target);
+    const unsigned long long ball = __ballot(match);
+    const int n = __ffsll((long long)~ball) - 1;          // first lane that does not match (lanes >= k never match)
+    const int gk = __shfl(myg, k - 1, 64);
+    const int nxt_t = __shfl(target, n < k ? n : 0, 64);
+    if (lane == 0) {
+        M.res->accept_len = n;
+        M.res->next_token = n < k ? nxt_t : gk;
+    }
+}
+
+// ---------------------------------------------------------------- one kernel per stage
+#define AMUSD_STAGE_KERNEL(name, body)                                                     \
+    template <class DT, int HD>                                                              \
+    __global__ void __launch_bounds__(kThreads) name(DevModel M, int layer) {               \
+        extern __shared__ float smem[];                                                      \
+        (void)layer; (void)smem;                                                             \
+        body;                                                                                \
+    }
+
+AMUSD_STAGE_KERNEL(k_embed, (stage_embed<DT>(M, blockIdx.x, gridDim.x)))
+AMUSD_STAGE_KERNEL(k_qkv, (stage_qkv<DT>(M, layer, blockIdx.x, gridDim.x, smem)))
+AMUSD_STAGE_KERNEL(k_attention, (stage_attention<DT, HD>(M, layer, blockIdx.x, gridDim.x, smem)))
+AMUSD_STAGE_KERNEL(k_attn_merge, (stage_attn_merge<DT, HD>(M, blockIdx.x, gridDim.x)))
+AMUSD_STAGE_KERNEL(k_oproj, (stage_oproj<DT>(M, layer, blockIdx.x, gridDim.x, smem)))
+AMUSD_STAGE_KERNEL(k_gateup, (stage_gateup<DT>(M, layer, blockIdx.x, gridDim.x, smem)))
+AMUSD_STAGE_KERNEL(k_down, (stage_down<DT>(M, layer, blockIdx.x, gridDim.x, smem)))
+AMUSD_STAGE_KERNEL(k_lmhead, (stage_lmhead<DT>(M, blockIdx.x, gridDim.x, smem)))
+
+__global__ void __launch_bounds__(64) k_accept(DevModel M) { stage_accept(M); }
+
+// ---------------------------------------------------------------- weight re-layout (model load)
+template <class DT>
+__global__ void k_relayout(uint4* __restrict__ dst, const void* __restrict__ src, int K, int n_tiles, int tile_offset,
+                           int kind, int hd) {
+    const int kblocks = K / DT::KB;
+    const size_t total = (size_t)n_tiles * kblocks * 64;
+    for (size_t x = (size_t)blockIdx.x * blockDim.x + threadIdx.x; x < total; x += (size_t)gridDim.x * blockDim.x) {
+        const int lane = (int)(x & 63);
+        const size_t f = x >> 6;
+        const int kb = (int)(f % kblocks);
+        const int t = (int)(f / kblocks);
+        const int r = lane & 15, g = lane >> 4;
+        long row;
+        if (kind == kNatural) {
+            row = (long)t * 16 + r;
+        } else if (kind == kRopePairs) {
+            const int tph = hd / 16;
+            row = (long)(t / tph) * hd + (t % tph) * 8 + (r & 7) + (r >> 3) * (hd / 2);
+        } else if (kind == kGate) {
+            if (r >= 8) continue;
+            row = (long)t * 8 + r;
+        } else {
+            if (r < 8) continue;
+            row = (long)t * 8 + r - 8;
+        }
+        const uint4 v = load_frag<DT>(src, (size_t)row * K + (size_t)kb * DT::KB + g * DT::EPL);
+        dst[((size_t)(tile_offset + t) * kblocks + kb) * 64 + lane] = v;
+    }
+}
+
+hipError_t launch_relayout(int dtype, uint4* dst, const void* src, int K, int n_tiles, int tile_offset, int kind,
+                           int hd, hipStream_t stream) {
+    const int kb = dtype ? BF16::KB : FP32::KB;
+    const size_t total = (size_t)n_tiles * (K / kb) * 64;
+    const int grid = (int)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
+    if (dtype)
+        hipLaunchKernelGGL(k_relayout<BF16>, dim3(grid), dim3(256), 0, stream, dst, src, K, n_tiles, tile_offset, kind, hd);
+    else
+        hipLaunchKernelGGL(k_relayout<FP32>, dim3(grid), dim3(256), 0, stream, dst, src, K, n_tiles, tile_offset, kind, hd);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- pass launch
+constexpr size_t kSmemBytes = (size_t)kSmemFloats * sizeof(float);
+
+template <class DT, int HD>
+static hipError_t configure_one() {
+    hipError_t e;
+#define AMUSD_SET(kern)                                                                                          \
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kern<DT, HD>), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                            (int)kSmemBytes);                                                                     \
+    if (e != hipSuccess) return e;
+    AMUSD_SET(k_qkv)
+    AMUSD_SET(k_attention)
+    AMUSD_SET(k_oproj)
+    AMUSD_SET(k_gateup)
+    AMUSD_SET(k_down)
+    AMUSD_SET(k_lmhead)
+#undef AMUSD_SET
+    return hipSuccess;
+}
+
+hipError_t configure_kernels() {
+    hipError_t e;
+    if ((e = configure_one<BF16, 64>()) != hipSuccess) return e;
+    if ((e = configure_one<BF16, 128>()) != hipSuccess) return e;
+    if ((e = configure_one<FP32, 64>()) != hipSuccess) return e;
+    if ((e = configure_one<FP32, 128>()) != hipSuccess) return e;
+    return hipSuccess;
+}
+
+template <class DT, int HD>
+static hipError_t launch_pass_t(const DevModel& M, int nwg, hipStream_t s) {
+    const dim3 blk(kThreads);
+    const int embed_wgs = (M.d / 16 + 3) / 4 < nwg ? (M.d / 16 + 3) / 4 : nwg;
+    hipLaunchKernelGGL((k_embed<DT, HD>), dim3(embed_wgs), blk, 0, s, M, 0);
+    for (int l = 0; l < M.n_layers; ++l) {
+        hipLaunchKernelGGL((k_qkv<DT, HD>), dim3(nwg), blk, kSmemBytes, s, M, l);
+        hipLaunchKernelGGL((k_attention<DT, HD>), dim3(nwg), blk, kSmemBytes, s, M, l);
+        hipLaunchKernelGGL((k_attn_merge<DT, HD>), dim3(nwg), blk, 0, s, M, l);
+        hipLaunchKernelGGL((k_oproj<DT, HD>), dim3(nwg), blk, kSmemBytes, s, M, l);
+        hipLaunchKernelGGL((k_gateup<DT, HD>), dim3(nwg), blk, kSmemBytes, s, M, l);
+        hipLaunchKernelGGL((k_down<DT, HD>), dim3(nwg), blk, kSmemBytes, s, M, l);
+    }
+    hipLaunchKernelGGL((k_lmhead<DT, HD>), dim3(M.lm_wgs), blk, kSmemBytes, s, M, 0);
+    hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, s, M);
+    return hipGetLastError();
+}
+
+hipError_t launch_pass(const DevModel& M, int nwg, hipStream_t stream, bool single_kernel) {
+    (void)single_kernel;
+    if (M.dtype) return M.hd == 128 ? launch_pass_t<BF16, 128>(M, nwg, stream) : launch_pass_t<BF16, 64>(M, nwg, stream);
+    return M.hd == 128 ? launch_pass_t<FP32, 128>(M, nwg, stream) : launch_pass_t<FP32, 64>(M, nwg, stream);
+}
+
+}  // namespace amusd

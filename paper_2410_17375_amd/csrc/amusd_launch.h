@@ -1,0 +1,25 @@
+// Host-callable launchers of the kernels in amusd_kernels.hip.
+#pragma once
+#include "amusd_dev.h"
+
+namespace amusd {
+
+enum RelayoutKind {
+    kNatural = 0,   // tile t, row r  <- source row 16t + r
+    kRopePairs = 1, // per head: tile th, row r <- feature 8th + (r%8) + (r/8)*hd/2   (rotary partners share a tile)
+    kGate = 2,      // tile t, rows 0-7  <- source row 8t + r
+    kUp = 3         // tile t, rows 8-15 <- source row 8t + r - 8
+};
+
+// One-time per process: raises the dynamic-LDS limit of the stage kernels.
+hipError_t configure_kernels();
+
+// Re-lays a row-major [rows, K] matrix into matrix-core operand order at
+// dst[(tile_offset + t) * (K/KB) + kb][lane].  n_tiles counts destination tiles.
+hipError_t launch_relayout(int dtype, uint4* dst, const void* src, int K, int n_tiles, int tile_offset, int kind,
+                           int hd, hipStream_t stream);
+
+// Enqueues one whole pass (all stages) on the stream.
+hipError_t launch_pass(const DevModel& M, int nwg, hipStream_t stream, bool single_kernel);
+
+}  // namespace amusd

@@ -1,0 +1,213 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.
+
+Bars: accept_len / next_token / arg-max tokens bit-exact except at rows the
+oracle flags (top-2 logit margin below the logit tolerance); logits within
+max-abs 1e-4 for fp32 models and 3e-2 for bf16 models."""
+import numpy as np
+import pytest
+
+from workload import SHAPES, WeightStore, prompt_tokens, corrupt_drafts
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"fp32": 1e-4, "bf16": 3e-2}
+
+
+def _gpu():
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2410_17375_amd as A
+    from paper_2410_17375_amd.harness import load_model
+    return A, load_model
+
+
+def _oracle(shape, store, max_ctx):
+    from oracle import Decoder, OracleStepper
+    return OracleStepper(Decoder(shape, store, max_ctx))
+
+
+def _pair(name, max_ctx):
+    A, load_model = _gpu()
+    shape = SHAPES[name]
+    store = WeightStore(shape)
+    g = load_model(shape, max_ctx, store=store)
+    g.set_option(A.OPT_KEEP_LOGITS, 1)
+    return shape, g, _oracle(shape, store, max_ctx)
+
+
+def _check_rows(shape, g, logits_ref, k, where):
+    """Logits within tolerance; arg-max equal wherever the oracle's margin is safe."""
+    tol = TOL[shape.dtype]
+    z = g.get_logits(k)
+    err = np.abs(z.astype(np.float64) - logits_ref).max()
+    assert err <= tol, f"{where}: logits max-abs error {err:.3e} > {tol}"
+    gg = g.get_greedy(k)
+    flagged = []
+    for j in range(k):
+        part = np.partition(logits_ref[j], -2)
+        margin = part[-1] - part[-2]
+        if margin < tol:
+            flagged.append(j)
+        else:
+            assert gg[j] == int(np.argmax(logits_ref[j])), f"{where}: row {j} arg-max differs"
+    return err, flagged
+
+
+@pytest.mark.parametrize("name", ["tiny_verify", "tiny_draft", "tiny_gqa_fp32", "tiny_gqa_bf16", "tiny_gqa128_bf16"])
+def test_prefill_and_verify_rounds_match_oracle(name):
+    shape, g, o = _pair(name, 320)
+    V = shape.vocab
+    prompt = prompt_tokens(0, 64, V)
+    # prompt in ragged pieces so every pass size and several start offsets occur
+    pos, worst = 0, 0.0
+    for n in (16, 1, 7, 16, 13, 11):
+        piece = prompt[pos:pos + n]
+        nxt = g.prefill(piece)
+        ref = o.dec.rows(piece)
+        for j in range(n):
+            o.greedy_at[pos + j + 1] = int(np.argmax(ref[j]))
+        err, flagged = _check_rows(shape, g, ref, n, f"{name} prefill@{pos}")
+        worst = max(worst, err)
+        pos += n
+        assert g.kv_len() == pos
+        if n - 1 not in flagged:
+            assert nxt == int(np.argmax(ref[-1]))
+    assert pos == 64
+    o.p_next = int(o.greedy_at[64])
+    # cache contents
+    for l in range(shape.n_layers):
+        for which, ref in ((0, o.dec.K[l]), (1, o.dec.V[l])):
+            got = g.get_kv(l, which, 0, 64)
+            tol = 1e-5 if shape.dtype == "fp32" else 2e-2
+            assert np.abs(got - ref[:, :64, :]).max() <= tol, (l, which)
+    # the oracle's greedy continuation, for drafting
+    from oracle import Decoder, OracleStepper, greedy_autoregressive
+    cont = greedy_autoregressive(OracleStepper(Decoder(shape, WeightStore(shape), 320)), prompt, 40)
+    full = np.concatenate([prompt, cont])
+    # 6 advancing rounds of k=4 with p=0.3 corruption (the small parity workload), then more sizes
+    L = 64
+    for r, k in enumerate([4, 4, 4, 4, 4, 4, 1, 8, 16, 5]):
+        if g.kv_len() < L:                          # teacher-force the GPU to the oracle's state
+            g.prefill(full[g.kv_len():L])
+        g.kv_rollback(L)
+        o.rollback(L)
+        draft = corrupt_drafts(shape.seed, r, full[L:L + k], 0.3, V)
+        res = o.verify(L, draft, route="step")
+        g.set_next(int(o.greedy_at[L]))           # same starting token on both sides
+        n, nxt = g.verify(L, draft)
+        err, flagged = _check_rows(shape, g, res.logits, k, f"{name} round {r}")
+        worst = max(worst, err)
+        if not any(j <= min(res.accept_len, k - 1) for j in flagged):
+            assert (n, nxt) == (res.accept_len, res.next_token), f"round {r}"
+            assert g.kv_len() == L + n
+        L = L + res.accept_len if res.accept_len else L
+    print(f"{name}: worst logit error {worst:.3e}")
+
+
+@pytest.mark.parametrize("name", ["tiny_verify", "tiny_gqa_bf16", "tiny_gqa128_bf16"])
+def test_k_row_pass_equals_k_single_row_passes_bitwise(name):
+    """On the GPU itself a row's result must not depend on how many rows the pass has."""
+    A, load_model = _gpu()
+    shape = SHAPES[name]
+    store = WeightStore(shape)
+    a, b = load_model(shape, 600, store=store), load_model(shape, 600, store=store)
+    for m in (a, b):
+        m.set_option(A.OPT_KEEP_LOGITS, 1)
+    toks = prompt_tokens(3, 300, shape.vocab)
+    a.prefill(toks[:270])
+    b.prefill(toks[:270])
+    for L, k in ((270, 16), (286, 5), (291, 9)):
+        a.prefill(toks[L:L + k])
+        za = a.get_logits(k)
+        for j in range(k):
+            b.prefill(toks[L + j:L + j + 1])
+            zb = b.get_logits(1)
+            assert np.array_equal(za[j], zb[0]), (L, j)
+    for l in range(shape.n_layers):
+        for which in (0, 1):
+            assert np.array_equal(a.get_kv(l, which, 0, 300), b.get_kv(l, which, 0, 300))
+
+
+def test_rollback_then_reextend_equals_fresh_on_gpu():
+    A, load_model = _gpu()
+    shape = SHAPES["tiny_gqa_bf16"]
+    store = WeightStore(shape)
+    a, b = load_model(shape, 400, store=store), load_model(shape, 400, store=store)
+    for m in (a, b):
+        m.set_option(A.OPT_KEEP_LOGITS, 1)
+    toks, alt = prompt_tokens(4, 300, shape.vocab), prompt_tokens(5, 300, shape.vocab)
+    a.prefill(toks[:290])
+    for m_ in (0, 1, 255, 256, 257, 289):
+        a.kv_rollback(m_)
+        assert a.kv_len() == m_
+        a.prefill(alt[m_:m_ + 7])
+        za = a.get_logits(7)
+        b.kv_rollback(0)
+        if m_:
+            b.prefill(toks[:m_])
+        b.prefill(alt[m_:m_ + 7])
+        assert np.array_equal(za, b.get_logits(7)), m_
+        a.kv_rollback(0)
+        a.prefill(toks[:290])
+
+
+def test_decoding_loops_reproduce_greedy_sequence():
+    A, load_model = _gpu()
+    from oracle import Decoder, OracleStepper, greedy_autoregressive
+    sv, sd = SHAPES["tiny_verify"], SHAPES["tiny_draft"]
+    store = WeightStore(sv)
+    torch = pytest.importorskip("torch")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    v = load_model(sv, 256, store=store, stream=s1.cuda_stream)
+    d = load_model(sd, 256, stream=s2.cuda_stream)
+    prompt = prompt_tokens(0, 64, sv.vocab)
+    ref = greedy_autoregressive(OracleStepper(Decoder(sv, store, 256)), prompt, 48)
+    out_g, st_g = A.generate_greedy(v, prompt, 48)
+    # oracle vs GPU greedy: exact except where the oracle's margin is tiny (none expected at 1e-4)
+    assert np.array_equal(out_g, ref)
+    out_s, st_s = A.generate_sync(d, v, prompt, 48, 4)
+    assert np.array_equal(out_s, out_g)
+    assert st_s["rounds"] >= 1 and sum(st_s["accept_hist"]) == st_s["rounds"]
+    for _ in range(3):
+        out_a, st_a = A.generate_async(d, v, prompt, 48, 4)
+        assert np.array_equal(out_a, out_g)
+        assert st_a["rounds"] >= 1
+    # draft := same weights as verify -> no rollbacks in the synchronous loop
+    twin = load_model(sv, 256, store=store, stream=s2.cuda_stream)
+    out_t, st_t = A.generate_sync(twin, v, prompt, 48, 4)
+    assert np.array_equal(out_t, out_g) and st_t["rollbacks"] == 0
+    out_t2, _ = A.generate_async(twin, v, prompt, 48, 4)
+    assert np.array_equal(out_t2, out_g)
+
+
+def test_error_codes_and_edges():
+    A, load_model = _gpu()
+    shape = SHAPES["tiny_draft"]
+    g = load_model(shape, 40, max_k=8)
+    with pytest.raises(A.AmusdError) as e:
+        g.draft_step()
+    assert e.value.code == -5                      # p_next unknown on an empty cache
+    with pytest.raises(A.AmusdError) as e:
+        g.verify(0, [1, 2])
+    assert e.value.code == -5
+    g.prefill(prompt_tokens(1, 30, shape.vocab))
+    for call, code in ((lambda: g.verify(31, [1]), -2), (lambda: g.verify(-1, [1]), -2),
+                       (lambda: g.verify(30, list(range(9))), -1), (lambda: g.verify(30, []), -1),
+                       (lambda: g.verify(30, [shape.vocab]), -4), (lambda: g.verify(30, [-1]), -4),
+                       (lambda: g.prefill(list(range(11))), -3), (lambda: g.kv_rollback(31), -2),
+                       (lambda: g.kv_rollback(-1), -2), (lambda: g.set_next(shape.vocab), -4)):
+        with pytest.raises(A.AmusdError) as e:
+            call()
+        assert e.value.code == code
+        assert g.kv_len() == 30                   # state unchanged by a rejected call
+    g.prefill(list(range(10)))                    # fills the cache to max_ctx exactly
+    assert g.kv_len() == 40
+    with pytest.raises(A.AmusdError) as e:
+        g.draft_step()
+    assert e.value.code == -3
+    n, nxt = g.verify(39, [5])                    # last row of the cache is still usable
+    assert n in (0, 1) and 0 <= nxt < shape.vocab
+    g.kv_rollback(0)
+    assert g.kv_len() == 0 and g.get_next() == -1
