@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the verify pass on one MI355X.
+
+A step is one whole verify pass (embedding, every decoder layer against the
+key-value cache, LM head, arg-max, prefix acceptance, cache truncation) of the
+8B-shape bf16 model, k=8 draft rows at context 2048, on seeded synthetic
+weights and tokens.  Every round starts from the same context (the cache is
+truncated back in O(1) by the call itself) with the greedy continuation
+re-corrupted with probability p.
+
+Prints one JSON line: latency, algorithmic HBM GB/s, accepted tokens/s, the
+roofline of the dominant kernel (HIP events around each of its launches inside
+the timed region) and the CPU oracle timed on the host cores as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "verify-pass latency (ms) + HBM GB/s, 8B-shape bf16 k=8 ctx2048; accepted tok/s"
+WORKLOADS = {
+    # name: (shape, context, k, seed)
+    "8b_bf16_k8_ctx2048": ("8b", 2048, 8, 2),
+    "1b_bf16_k5_ctx512": ("1b", 512, 5, 1),
+    "8b_bf16_k16_ctx16384": ("8b", 16384, 16, 3),
+    "tiny_fp32_k4_ctx64": ("tiny_verify", 64, 4, 0),
+}
+HBM_PEAK_GBPS = 8000.0
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def cpu_baseline(shape, L0, k, draft, target_seconds=20.0):
+    """The oracle's verify pass (batched route, float32) timed on the host
+    cores, on a bounded sample: the pass over the first 1 and the first 3
+    layers (+ LM head) of the same model at the same context, extrapolated
+    linearly in the layer count.  The cache is filled with random values: its
+    contents do not change the work."""
+    from oracle import Decoder
+    from workload import WeightStore
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    rng = np.random.default_rng(0)
+    times = {}
+    for nl in (1, 3):
+        sub = shape.with_(n_layers=nl)
+        store = WeightStore(sub, cache=True)
+        dec = Decoder(sub, store, L0 + k, dtype=np.float32, keep_weights=True)
+        for l in range(nl):
+            dec.K[l][:, :L0, :] = rng.standard_normal((sub.n_kv_heads, L0, sub.head_dim), dtype=np.float32)
+            dec.V[l][:, :L0, :] = rng.standard_normal((sub.n_kv_heads, L0, sub.head_dim), dtype=np.float32)
+        dec.kv_len = L0
+        dec.rows(draft)                      # fetches and converts the weights; untimed
+        best, reps, t_start = None, 0, time.perf_counter()
+        while reps < 3 or (time.perf_counter() - t_start < target_seconds / 4 and reps < 20):
+            dec.rollback(L0)
+            t0 = time.perf_counter()
+            dec.rows(draft)
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+            reps += 1
+        times[nl] = best
+        log(f"cpu_baseline: {nl}-layer oracle pass {best * 1e3:.1f} ms (best of {reps})")
+        del dec, store
+    per_layer = (times[3] - times[1]) / 2.0
+    full = times[1] + per_layer * (shape.n_layers - 1)
+    return {"value": full * 1e3, "unit": "ms", "cores": int(cores), "kind": "oracle",
+            "sample": f"oracle batched k={k} pass at ctx {L0}, float32, timed on the first 1 and 3 layers + LM head "
+                      f"of the same weights (best of >=3), extrapolated linearly to {shape.n_layers} layers; "
+                      f"cache filled with random values",
+            "measured_ms": {"layers_1": times[1] * 1e3, "layers_3": times[3] * 1e3}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="8b_bf16_k8_ctx2048", choices=sorted(WORKLOADS))
+    ap.add_argument("--p", type=float, default=0.3, help="draft corruption probability")
+    ap.add_argument("--single-kernel", type=int, default=0)
+    ap.add_argument("--time-stage", default="gateup", help="stage bracketed with HIP events ('none' to disable)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    import paper_2410_17375_amd as A
+    from paper_2410_17375_amd.harness import load_model
+    from workload import SHAPES, prompt_tokens, corrupt_drafts
+
+    shape_name, L0, k, seed = WORKLOADS[args.workload]
+    shape = SHAPES[shape_name]
+    stream = torch.cuda.Stream()
+    t0 = time.perf_counter()
+    log(f"loading {shape_name} ({shape.n_params_streamed() / 1e9:.2f} G weights) ...")
+    model = load_model(shape, L0 + A.MAX_K, stream=stream.cuda_stream, progress=log)
+    log(f"model loaded in {time.perf_counter() - t0:.1f} s")
+    model.set_option(A.OPT_SINGLE_KERNEL, args.single_kernel)
+
+    prompt = prompt_tokens(seed, L0, shape.vocab)
+    t0 = time.perf_counter()
+    first = model.prefill(prompt)
+    log(f"context of {L0} tokens prefilled in {time.perf_counter() - t0:.2f} s")
+    cont = [first]
+    for _ in range(k - 1):
+        cont.append(model.draft_step())
+    model.kv_rollback(L0)
+    drafts = [corrupt_drafts(seed, r, cont, args.p, shape.vocab) for r in range(args.warmup + args.steps)]
+
+    for r in range(args.warmup):
+        model.verify(L0, drafts[r])
+    if args.time_stage != "none":
+        model.set_option(A.OPT_TIME_STAGE, A.STAGES[args.time_stage])
+    host_ms, dev_ms, accepts = [], [], []
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for r in range(args.warmup, args.warmup + args.steps):
+        t1 = time.perf_counter()
+        n, _ = model.verify(L0, drafts[r])
+        host_ms.append((time.perf_counter() - t1) * 1e3)
+        dev_ms.append(model.last_pass_ms())
+        accepts.append(n)
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t_begin
+    ms_per_step = total_s * 1e3 / args.steps
+
+    bytes_pass = model.weight_bytes_per_pass() + model.kv_bytes_per_pass(L0, k) \
+        + k * shape.d_model * shape.weight_elem_bytes \
+        + shape.n_layers * 2 * shape.kv_dim * shape.weight_elem_bytes * k
+    gbps = bytes_pass / (ms_per_step * 1e-3) / 1e9
+    hist = np.bincount(accepts, minlength=k + 1).tolist()
+    out = {
+        "metric": METRIC, "value": round(ms_per_step, 4), "unit": "ms", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if shape.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "shape": shape_name, "ctx": L0, "k": k, "corruption_p": args.p,
+                   "seed": seed, "mode": "single_kernel" if args.single_kernel else "kernel_per_stage"},
+        "latency_ms": {"host_median": round(float(np.median(host_ms)), 4),
+                       "host_p10": round(float(np.percentile(host_ms, 10)), 4),
+                       "host_p90": round(float(np.percentile(host_ms, 90)), 4),
+                       "device_median": round(float(np.median(dev_ms)), 4)},
+        "algorithmic_bytes_per_pass": int(bytes_pass),
+        "hbm_gbps": round(gbps, 1), "hbm_frac_of_8TBps": round(gbps / HBM_PEAK_GBPS, 4),
+        "accepted_tok_per_s": round(sum(accepts) / total_s, 1),
+        "accept_hist": hist, "mean_accept_len": round(float(np.mean(accepts)), 3),
+    }
+    if args.time_stage != "none":
+        ms, launches, b = model.stage_time()
+        avg_ms = ms / max(launches, 1)
+        ach = b / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
+        out["roofline"] = {"bound": "hbm", "kernel": args.time_stage, "achieved": round(ach, 1),
+                           "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
+                           "traffic": None, "avg_launch_ms": round(avg_ms, 5), "launches": int(launches),
+                           "algorithmic_bytes_per_launch": int(b)}
+    if not args.no_cpu_baseline:
+        try:
+            out["cpu_baseline"] = cpu_baseline(shape, L0, k, drafts[0])
+            out["cpu_baseline"]["accepted_tok_per_s"] = round(
+                float(np.mean(accepts)) / (out["cpu_baseline"]["value"] * 1e-3), 2)
+        except MemoryError as e:          # pragma: no cover
+            out["cpu_baseline"] = {"value": None, "error": repr(e)}
+    model.free()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

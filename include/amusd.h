@@ -67,12 +67,20 @@ enum {
 /* Options for amusd_set_option. */
 enum {
     AMUSD_OPT_KEEP_LOGITS = 0, /* 1: each pass also stores its fp32 logits (test hook), default 0 */
-    AMUSD_OPT_SINGLE_KERNEL = 1 /* 1: one persistent kernel per pass; 0: one kernel per stage */
+    AMUSD_OPT_SINGLE_KERNEL = 1, /* 1: one persistent kernel per pass; 0: one kernel per stage */
+    AMUSD_OPT_TIME_STAGE = 2    /* AMUSD_STAGE_* to bracket with HIP events in every pass, -1: none (default) */
+};
+
+/* Stages of a pass, for AMUSD_OPT_TIME_STAGE / amusd_stage_time. */
+enum {
+    AMUSD_STAGE_EMBED = 0, AMUSD_STAGE_QKV = 1, AMUSD_STAGE_ATTENTION = 2, AMUSD_STAGE_ATTN_MERGE = 3,
+    AMUSD_STAGE_OPROJ = 4, AMUSD_STAGE_GATEUP = 5, AMUSD_STAGE_DOWN = 6, AMUSD_STAGE_LMHEAD = 7,
+    AMUSD_STAGE_ACCEPT = 8, AMUSD_STAGE_COUNT = 9
 };
 
 typedef struct amusd_model amusd_model; /* opaque, owned by the library */
 
-/* Decoder shape.  Requirements: n_q_heads % n_kv_heads == 0; head_dim is 64 or
+/* Decoder shape.  Requirements: n_q_heads / n_kv_heads is 1, 2, 4 or 8; head_dim is 64 or
  * 128; d_model, n_q_heads*head_dim and d_ffn are multiples of 32 (bf16) or 16
  * (fp32); vocab and d_ffn multiples of 16; 1 <= max_k <= AMUSD_MAX_K. */
 typedef struct {
@@ -203,6 +211,13 @@ int amusd_get_greedy(amusd_model *m, int32_t *out, int32_t rows);
 /* Device time of the last pass in milliseconds, from HIP events recorded on
  * the model's stream around the pass's kernels (first launch to last end). */
 int amusd_last_pass_ms(amusd_model *m, float *ms);
+
+/* Accumulated device time (HIP events on the model's stream, one pair around
+ * every launch of the stage selected with AMUSD_OPT_TIME_STAGE) and number of
+ * launches since the option was last set.  Also reports the algorithmic bytes
+ * one such launch reads from device memory (weights of the stage for one
+ * layer; for the attention stage the cache rows of the last pass). */
+int amusd_stage_time(amusd_model *m, double *total_ms, int64_t *launches, int64_t *bytes_per_launch);
 
 /* Copies rows [pos0, pos0+n) of layer `layer`'s cached keys (which=0) or
  * values (which=1) to host fp32 [n_kv_heads, n, head_dim], undoing the

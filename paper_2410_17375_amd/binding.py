@@ -9,7 +9,9 @@ _LIB_PATH = os.path.join(_HERE, "libamusd.so")
 
 DTYPE_FP32, DTYPE_BF16 = 0, 1
 MAX_K = 16
-OPT_KEEP_LOGITS, OPT_SINGLE_KERNEL = 0, 1
+OPT_KEEP_LOGITS, OPT_SINGLE_KERNEL, OPT_TIME_STAGE = 0, 1, 2
+STAGES = {"embed": 0, "qkv": 1, "attention": 2, "attn_merge": 3, "oproj": 4, "gateup": 5, "down": 6,
+          "lmhead": 7, "accept": 8}
 TENSOR_IDS = {"embed": 0, "lm_head": 1, "final_norm": 2, "wq": 3, "wk": 4, "wv": 5, "wo": 6,
               "wg": 7, "wu": 8, "wd": 9, "norm_attn": 10, "norm_mlp": 11}
 
@@ -77,6 +79,7 @@ def _load():
         "amusd_get_logits": (C.c_int, [vp, f32p, i32]),
         "amusd_get_greedy": (C.c_int, [vp, i32p, i32]),
         "amusd_last_pass_ms": (C.c_int, [vp, f32p]),
+        "amusd_stage_time": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]),
         "amusd_get_kv": (C.c_int, [vp, i32, i32, i32, i32, f32p]),
         "amusd_weight_bytes_per_pass": (C.c_int64, [vp]),
         "amusd_kv_bytes_per_pass": (C.c_int64, [vp, i32, i32]),
@@ -185,6 +188,12 @@ class Model:
         ms = C.c_float(0)
         _check(lib.amusd_last_pass_ms(self._h, C.byref(ms)))
         return ms.value
+
+    def stage_time(self):
+        """(total ms, launches, algorithmic bytes per launch) of the stage chosen with OPT_TIME_STAGE."""
+        ms, n, b = C.c_double(0), C.c_int64(0), C.c_int64(0)
+        _check(lib.amusd_stage_time(self._h, C.byref(ms), C.byref(n), C.byref(b)))
+        return ms.value, n.value, b.value
 
     def get_kv(self, layer, which, pos0, n):
         out = np.empty((self.cfg.n_kv_heads, n, self.cfg.head_dim), dtype=np.float32)

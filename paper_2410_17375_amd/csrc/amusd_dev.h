@@ -61,7 +61,7 @@ struct DevModel {
     float* ssq;           // [d/16][16] partial sums of squares of X rows
     void* Q_hi;           // [16][qdim]
     void* Q_lo;
-    float* att_part;      // [units][G][16][hd+2]: (max, denominator, numerator[hd])
+    float* att_part;      // [units][G][16][hd+4]: numerator[hd], max, denominator, 2 pad
     void* O_hi;           // merged attention output [16][qdim]
     void* O_lo;
     void* H_hi;           // SwiGLU output [16][F]

@@ -72,6 +72,11 @@ struct amusd_model {
     size_t staging_bytes = 0;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     float last_ms = 0.f;
+    StageTimer timer;
+    std::vector<hipEvent_t> tev_begin, tev_end;
+    double stage_ms = 0.0;
+    int64_t stage_launches = 0;
+    int last_L = 0;
     int esz() const { return cfg.dtype == AMUSD_DTYPE_BF16 ? 2 : 4; }
     int kb() const { return cfg.dtype == AMUSD_DTYPE_BF16 ? 32 : 16; }
     int block_keys() const { return cfg.dtype == AMUSD_DTYPE_BF16 ? 32 : 16; }
@@ -94,6 +99,11 @@ int check_config(const amusd_config* c) {
     if (c->max_k < 1 || c->max_k > AMUSD_MAX_K) return fail(AMUSD_E_ARG, "config: max_k outside [1,16]");
     if (c->head_dim != 64 && c->head_dim != 128) return fail(AMUSD_E_ARG, "config: head_dim must be 64 or 128");
     if (c->n_q_heads % c->n_kv_heads) return fail(AMUSD_E_ARG, "config: n_q_heads not a multiple of n_kv_heads");
+    {
+        const int G = c->n_q_heads / c->n_kv_heads;
+        if (G != 1 && G != 2 && G != 4 && G != 8)
+            return fail(AMUSD_E_ARG, "config: n_q_heads / n_kv_heads must be 1, 2, 4 or 8");
+    }
     const int kb = c->dtype == AMUSD_DTYPE_BF16 ? 32 : 16;
     const long qdim = (long)c->n_q_heads * c->head_dim;
     if (c->d_model % kb || qdim % kb || c->d_ffn % kb)
@@ -152,11 +162,20 @@ int run_pass(amusd_model* m, int L, const int32_t* tokens, int k, bool force_acc
     h->pp.p_ctx = m->greedy_at[L];
     HIP_TRY(hipEventRecord(m->ev0, m->stream));
     HIP_TRY(hipMemcpyAsync(m->dstage, h, sizeof(DevStage), hipMemcpyHostToDevice, m->stream));
-    HIP_TRY(launch_pass(m->dm, m->nwg, m->stream, m->single_kernel));
+    HIP_TRY(launch_pass(m->dm, m->nwg, m->stream, m->single_kernel, m->timer.stage >= 0 ? &m->timer : nullptr));
     HIP_TRY(hipMemcpyAsync(&h->res, m->dm.res, sizeof(PassResult), hipMemcpyDeviceToHost, m->stream));
     HIP_TRY(hipEventRecord(m->ev1, m->stream));
     HIP_TRY(hipStreamSynchronize(m->stream));
     HIP_TRY(hipEventElapsedTime(&m->last_ms, m->ev0, m->ev1));
+    if (m->timer.stage >= 0) {
+        for (int i = 0; i < m->timer.used; ++i) {
+            float ms = 0.f;
+            HIP_TRY(hipEventElapsedTime(&ms, m->timer.begin[i], m->timer.end[i]));
+            m->stage_ms += ms;
+        }
+        m->stage_launches += m->timer.used;
+    }
+    m->last_L = L;
     m->logits_valid = m->keep_logits;
     m->last_rows = k;
     for (int j = 0; j < k; ++j) m->greedy_at[L + j + 1] = h->res.greedy[j];
@@ -223,7 +242,7 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
     m->nwg = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
 
     const amusd_config& c = m->cfg;
-    const int esz = m->esz(), kb = m->kb(), BK = m->block_keys();
+    const int esz = m->esz(), BK = m->block_keys();
     DevModel& D = m->dm;
     D.n_layers = c.n_layers; D.d = c.d_model; D.Hq = c.n_q_heads; D.Hkv = c.n_kv_heads; D.hd = c.head_dim;
     D.F = c.d_ffn; D.V = c.vocab; D.G = c.n_q_heads / c.n_kv_heads;
@@ -270,7 +289,7 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
     ALLOC(D.ssq, float*, (d / 16) * kRows * 4, true)
     ALLOC(D.Q_hi, void*, kRows * q * 4, true)
     ALLOC(D.Q_lo, void*, kRows * q * 4, true)
-    ALLOC(D.att_part, float*, (size_t)D.Hkv * D.max_chunks * D.G * kRows * (D.hd + 2) * 4, true)
+    ALLOC(D.att_part, float*, (size_t)D.Hkv * D.max_chunks * D.G * kRows * (D.hd + 4) * 4, true)
     ALLOC(D.O_hi, void*, kRows * q * 4, true)
     ALLOC(D.O_lo, void*, kRows * q * 4, true)
     ALLOC(D.H_hi, void*, kRows * F * 4, true)
@@ -435,6 +454,8 @@ int amusd_model_free(amusd_model* m) {
     if (m->hstage) (void)hipHostFree(m->hstage);
     if (m->ev0) (void)hipEventDestroy(m->ev0);
     if (m->ev1) (void)hipEventDestroy(m->ev1);
+    for (hipEvent_t e : m->tev_begin) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : m->tev_end) if (e) (void)hipEventDestroy(e);
     delete m;
     return AMUSD_OK;
 }
@@ -510,6 +531,23 @@ int amusd_set_option(amusd_model* m, int32_t option, int32_t value) {
     switch (option) {
         case AMUSD_OPT_KEEP_LOGITS: m->keep_logits = value != 0; return AMUSD_OK;
         case AMUSD_OPT_SINGLE_KERNEL: m->single_kernel = value != 0; return AMUSD_OK;
+        case AMUSD_OPT_TIME_STAGE: {
+            if (value < -1 || value >= AMUSD_STAGE_COUNT) return fail(AMUSD_E_ARG, "unknown stage");
+            if (value >= 0 && m->tev_begin.empty()) {
+                m->tev_begin.resize(m->cfg.n_layers);
+                m->tev_end.resize(m->cfg.n_layers);
+                for (int i = 0; i < m->cfg.n_layers; ++i) {
+                    HIP_TRY(hipEventCreate(&m->tev_begin[i]));
+                    HIP_TRY(hipEventCreate(&m->tev_end[i]));
+                }
+                m->timer.begin = m->tev_begin.data();
+                m->timer.end = m->tev_end.data();
+            }
+            m->timer.stage = value;
+            m->stage_ms = 0.0;
+            m->stage_launches = 0;
+            return AMUSD_OK;
+        }
         default: return fail(AMUSD_E_ARG, "unknown option");
     }
 }
@@ -534,6 +572,28 @@ int amusd_get_greedy(amusd_model* m, int32_t* out, int32_t rows) {
 int amusd_last_pass_ms(amusd_model* m, float* ms) {
     if (!m || !ms) return fail(AMUSD_E_ARG, "null argument");
     *ms = m->last_ms;
+    return AMUSD_OK;
+}
+
+int amusd_stage_time(amusd_model* m, double* total_ms, int64_t* launches, int64_t* bytes_per_launch) {
+    if (!m || !total_ms || !launches || !bytes_per_launch) return fail(AMUSD_E_ARG, "null argument");
+    if (m->timer.stage < 0) return fail(AMUSD_E_STATE, "no stage selected for timing");
+    const amusd_config& c = m->cfg;
+    const int64_t d = c.d_model, q = (int64_t)c.n_q_heads * c.head_dim, kv = (int64_t)c.n_kv_heads * c.head_dim,
+                  F = c.d_ffn, V = c.vocab, e = m->esz();
+    int64_t b = 0;
+    switch (m->timer.stage) {
+        case AMUSD_STAGE_QKV: b = d * (q + 2 * kv) * e; break;
+        case AMUSD_STAGE_ATTENTION: b = 2 * kv * e * ((int64_t)m->last_L + m->last_rows); break;
+        case AMUSD_STAGE_OPROJ: b = q * d * e; break;
+        case AMUSD_STAGE_GATEUP: b = 2 * d * F * e; break;
+        case AMUSD_STAGE_DOWN: b = d * F * e; break;
+        case AMUSD_STAGE_LMHEAD: b = V * d * e; break;
+        default: b = 0;
+    }
+    *total_ms = m->stage_ms;
+    *launches = m->stage_launches;
+    *bytes_per_launch = b;
     return AMUSD_OK;
 }
 

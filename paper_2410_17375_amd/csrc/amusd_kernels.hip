@@ -81,88 +81,154 @@ __device__ __forceinline__ uint4 load_frag(const void* base, size_t elem_index) 
 __device__ __forceinline__ float wave_xor_add(float v, int off) { return v + __shfl_xor(v, off, 64); }
 
 // ---------------------------------------------------------------- RMS scale of the 16 rows
-// Sums the per-tile partial sums of squares in a fixed order and leaves
-// 1/sqrt(mean + eps) for each row in rstd[16] (LDS).  512 threads.
-__device__ __forceinline__ void compute_rstd(const DevModel& M, float* rstd) {
-    const int tid = threadIdx.x;
-    const int m = tid >> 5, s = tid & 31;
-    const int ntp = M.d / 16;
-    float acc = 0.f;
-    for (int t = s; t < ntp; t += 32) acc += M.ssq[t * kRows + m];
-    acc = wave_xor_add(acc, 16);
-    acc = wave_xor_add(acc, 8);
-    acc = wave_xor_add(acc, 4);
-    acc = wave_xor_add(acc, 2);
-    acc = wave_xor_add(acc, 1);
-    if (s == 0) rstd[m] = 1.0f / sqrtf(acc / (float)M.d + M.eps);
-    __syncthreads();
-}
+// The per-tile partial sums of squares are fetched at the start of a stage
+// (so the fetch is the oldest entry of the load queue and never stalls the
+// weight stream) and reduced in a fixed order just before the epilogue.
+// Thread (row m = tid/32, slot s = tid%32) sums tiles s, s+32, ..; 512 threads.
+struct RstdPrefetch {
+    static constexpr int N = 8;      // covers d <= 4096 from registers; larger d loops in finish()
+    float v[N];
+    __device__ __forceinline__ void begin(const DevModel& M) {
+        const int m = threadIdx.x >> 5, s = threadIdx.x & 31;
+        const int ntp = M.d / 16;
+#pragma unroll
+        for (int t = 0; t < N; ++t) {
+            const int idx = s + 32 * t;
+            const float x = M.ssq[(idx < ntp ? idx : ntp - 1) * kRows + m];
+            v[t] = idx < ntp ? x : 0.f;
+        }
+    }
+    __device__ __forceinline__ void finish(const DevModel& M, float* rstd) {
+        const int m = threadIdx.x >> 5, s = threadIdx.x & 31;
+        const int ntp = M.d / 16;
+        float acc = 0.f;
+#pragma unroll
+        for (int t = 0; t < N; ++t) acc += v[t];
+        for (int idx = s + 32 * N; idx < ntp; idx += 32) acc += M.ssq[idx * kRows + m];
+        acc = wave_xor_add(acc, 16);
+        acc = wave_xor_add(acc, 8);
+        acc = wave_xor_add(acc, 4);
+        acc = wave_xor_add(acc, 2);
+        acc = wave_xor_add(acc, 1);
+        if (s == 0) rstd[m] = 1.0f / sqrtf(acc / (float)M.d + M.eps);
+    }
+};
 
 // ---------------------------------------------------------------- skinny GEMM stage
 // C[n][m] = sum_k W[n][k] * A[m][k] for the 16 rows m, output tiles of 16
-// columns n.  Workgroup wg owns tiles wg, wg+nwg, ...; up to 8 at a time.
+// columns n.  Workgroup wg owns tiles wg, wg+nwg, ...; up to 8 per round.
 // Wave w contracts over its slice of the K blocks; partial tiles are summed
 // through LDS in wave order, then epi.item() runs on every pair
 // (column r, column r+8) of each tile.
+//
+// The contraction loop is a software pipeline of D stages, one stage = one K
+// block = NT weight fragments + the activation fragment(s).  All loads are
+// unconditional (out-of-range stages re-read the last stage and multiply by a
+// zeroed activation), so the loop body is straight-line code and the hardware
+// load queue stays D stages deep: with 8 waves per CU that is 64-128 KiB of
+// weight bytes in flight per CU, what it takes to cover HBM latency at 8 TB/s.
+template <class DT, int NT, int D>
+__device__ __forceinline__ void gemm_accumulate(v4f (&acc)[kMaxTilesPerRound], const uint4* __restrict__ W, int tile0,
+                                                int tile_stride, int kblocks, int kb0, int S,
+                                                const char* __restrict__ ah, const char* __restrict__ al, int lane) {
+    constexpr size_t ASTEP = (size_t)DT::KB * DT::ESZ;   // bytes of one K block of one activation row
+    const uint4* wp[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) wp[j] = W + ((size_t)(tile0 + tile_stride * j) * kblocks + kb0) * 64 + lane;
+    uint4 wb[D][NT], bh[D], bl[D];
+    const int last = S - 1;
+#pragma unroll
+    for (int i = 0; i < D; ++i) {
+        const int s = i < last ? i : last;
+#pragma unroll
+        for (int j = 0; j < NT; ++j) wb[i][j] = wp[j][(size_t)s * 64];
+        bh[i] = *reinterpret_cast<const uint4*>(ah + s * ASTEP);
+        if constexpr (DT::HAS_LO) bl[i] = *reinterpret_cast<const uint4*>(al + s * ASTEP);
+    }
+    int s0 = 0;
+    for (; s0 + D < S; s0 += D) {
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                acc[j] = DT::mfma(wb[i][j], bh[i], acc[j]);
+                if constexpr (DT::HAS_LO) acc[j] = DT::mfma(wb[i][j], bl[i], acc[j]);
+            }
+            const int sn = s0 + i + D < last ? s0 + i + D : last;
+#pragma unroll
+            for (int j = 0; j < NT; ++j) wb[i][j] = wp[j][(size_t)sn * 64];
+            bh[i] = *reinterpret_cast<const uint4*>(ah + sn * ASTEP);
+            if constexpr (DT::HAS_LO) bl[i] = *reinterpret_cast<const uint4*>(al + sn * ASTEP);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < D; ++i) {
+        const bool on = s0 + i < S;
+        const uint4 z = uint4{0, 0, 0, 0};
+        const uint4 h = on ? bh[i] : z;
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            acc[j] = DT::mfma(wb[i][j], h, acc[j]);
+            if constexpr (DT::HAS_LO) acc[j] = DT::mfma(wb[i][j], on ? bl[i] : z, acc[j]);
+        }
+    }
+}
+
 template <class DT, class Epi>
 __device__ __forceinline__ void gemm_stage(const uint4* __restrict__ W, int n_tiles, int kblocks,
                                            const void* __restrict__ Ahi, const void* __restrict__ Alo, int lda,
                                            int k_rows, int wg, int nwg, Epi& epi, float* smem) {
-    constexpr int NT = kMaxTilesPerRound;
+    constexpr int NTMAX = kMaxTilesPerRound;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
     const int kb0 = (kblocks * wave) / kWaves, kb1 = (kblocks * (wave + 1)) / kWaves;
+    const int S = kb1 - kb0;
     const int mine = wg < n_tiles ? (n_tiles - wg + nwg - 1) / nwg : 0;
-    const bool row_on = m < k_rows;
-    for (int i0 = 0; i0 < mine; i0 += NT) {
-        const int nt = min(NT, mine - i0);
-        v4f acc[NT];
-        const uint4* wp[NT];
+    // rows >= k re-read row k-1 (same cache lines, no extra traffic); their results are never used
+    const int mrow = m < k_rows ? m : k_rows - 1;
+    const size_t aoff = ((size_t)mrow * lda + (size_t)g * DT::EPL + (size_t)kb0 * DT::KB) * DT::ESZ;
+    const char* ah = reinterpret_cast<const char*>(Ahi) + aoff;
+    const char* al = reinterpret_cast<const char*>(Alo) + aoff;
+    bool first = true;
+    for (int i0 = 0; i0 < mine;) {
+        const int left = mine - i0;
+        const int nt = left >= 8 ? 8 : left == 7 ? 7 : left >= 4 ? 4 : left >= 2 ? 2 : 1;
+        v4f acc[NTMAX];
 #pragma unroll
-        for (int j = 0; j < NT; ++j) {
-            acc[j] = v4f{0.f, 0.f, 0.f, 0.f};
-            const int t = wg + nwg * (i0 + (j < nt ? j : 0));
-            wp[j] = W + ((size_t)t * kblocks + kb0) * 64 + lane;
-        }
-        const size_t abase = (size_t)m * lda + (size_t)g * DT::EPL;
-#pragma unroll 2
-        for (int kb = kb0; kb < kb1; ++kb) {
-            uint4 bh = uint4{0, 0, 0, 0}, bl = uint4{0, 0, 0, 0};
-            if (row_on) {
-                bh = load_frag<DT>(Ahi, abase + (size_t)kb * DT::KB);
-                if constexpr (DT::HAS_LO) bl = load_frag<DT>(Alo, abase + (size_t)kb * DT::KB);
+        for (int j = 0; j < NTMAX; ++j) acc[j] = v4f{0.f, 0.f, 0.f, 0.f};
+        if (S > 0) {
+            const int t0 = wg + nwg * i0;
+            switch (nt) {
+                case 8: gemm_accumulate<DT, 8, 2>(acc, W, t0, nwg, kblocks, kb0, S, ah, al, lane); break;
+                case 7: gemm_accumulate<DT, 7, 2>(acc, W, t0, nwg, kblocks, kb0, S, ah, al, lane); break;
+                case 4: gemm_accumulate<DT, 4, 4>(acc, W, t0, nwg, kblocks, kb0, S, ah, al, lane); break;
+                case 2: gemm_accumulate<DT, 2, 8>(acc, W, t0, nwg, kblocks, kb0, S, ah, al, lane); break;
+                default: gemm_accumulate<DT, 1, 8>(acc, W, t0, nwg, kblocks, kb0, S, ah, al, lane); break;
             }
-            uint4 a[NT];
-#pragma unroll
-            for (int j = 0; j < NT; ++j)
-                if (j < nt) a[j] = wp[j][(size_t)(kb - kb0) * 64];
-#pragma unroll
-            for (int j = 0; j < NT; ++j)
-                if (j < nt) {
-                    acc[j] = DT::mfma(a[j], bh, acc[j]);
-                    if constexpr (DT::HAS_LO) acc[j] = DT::mfma(a[j], bl, acc[j]);
-                }
         }
         // partial tiles to LDS as [wave][tile][m][n]; lane holds n = 4g..4g+3 of row m
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
-            if (j < nt) *reinterpret_cast<v4f*>(smem + ((wave * NT + j) * 256 + m * 16 + g * 4)) = acc[j];
+        for (int j = 0; j < NTMAX; ++j)
+            if (j < nt) *reinterpret_cast<v4f*>(smem + ((wave * NTMAX + j) * 256 + m * 16 + g * 4)) = acc[j];
+        if (first) epi.prepare();
+        first = false;
         __syncthreads();
-        for (int item = tid; item < NT * 128; item += kThreads) {
+        for (int item = tid; item < NTMAX * 128; item += kThreads) {
             const int j = item >> 7, mm = (item >> 3) & 15, r = item & 7;
             const bool valid = j < nt;
             float v1 = 0.f, v2 = 0.f;
             if (valid) {
 #pragma unroll
                 for (int w = 0; w < kWaves; ++w) {
-                    v1 += smem[(w * NT + j) * 256 + mm * 16 + r];
-                    v2 += smem[(w * NT + j) * 256 + mm * 16 + r + 8];
+                    v1 += smem[(w * NTMAX + j) * 256 + mm * 16 + r];
+                    v2 += smem[(w * NTMAX + j) * 256 + mm * 16 + r + 8];
                 }
             }
             epi.item(wg + nwg * (i0 + (valid ? j : 0)), j, mm, r, v1, v2, valid);
         }
         __syncthreads();
         epi.round_end(nt);
+        i0 += nt;
     }
 }
 
@@ -201,6 +267,7 @@ struct EpiResidual {   // O-projection and down-projection: X += C, feed the nex
         }
         residual_pair<DT>(M, gain_next, tile, mm, r, x1, x2, k_rows, valid);
     }
+    __device__ __forceinline__ void prepare() {}
     __device__ __forceinline__ void round_end(int) {}
 };
 
@@ -208,8 +275,10 @@ template <class DT>
 struct EpiQKV {        // RMS scale, rotary embedding on (i, i+hd/2) pairs, Q to its buffer, K/V appended to the cache
     const DevModel& M;
     const DevLayer& Ly;
-    const float* rstd;   // LDS
+    float* rstd;         // LDS
     int L, k_rows;
+    RstdPrefetch pre;
+    __device__ __forceinline__ void prepare() { pre.finish(M, rstd); }
     __device__ __forceinline__ void item(int tile, int /*slot*/, int mm, int r, float v1, float v2, bool valid) {
         if (!valid || mm >= k_rows) return;
         const int hd = M.hd, tph = hd / 16;
@@ -261,8 +330,10 @@ struct EpiQKV {        // RMS scale, rotary embedding on (i, i+hd/2) pairs, Q to
 template <class DT>
 struct EpiSwiGLU {     // tile rows 0-7 are gate features, 8-15 the matching up features
     const DevModel& M;
-    const float* rstd;
+    float* rstd;
     int k_rows;
+    RstdPrefetch pre;
+    __device__ __forceinline__ void prepare() { pre.finish(M, rstd); }
     __device__ __forceinline__ void item(int tile, int /*slot*/, int mm, int r, float v1, float v2, bool valid) {
         if (!valid || mm >= k_rows) return;
         const float sc = rstd[mm];
@@ -290,6 +361,8 @@ struct EpiLMHead {     // logits (optionally stored); per-row arg-max over this 
     int k_rows, keep;
     float run_v;         // thread mm < 16 keeps the workgroup's running best for row mm
     int run_i;
+    RstdPrefetch pre;
+    __device__ __forceinline__ void prepare() { pre.finish(M, smem + kOffRstd); }
     __device__ __forceinline__ void item(int tile, int slot, int mm, int r, float v1, float v2, bool valid) {
         const float sc = smem[kOffRstd + mm];
         const float z1 = v1 * sc, z2 = v2 * sc;
@@ -355,8 +428,8 @@ __device__ __forceinline__ void stage_embed(const DevModel& M, int wg, int nwg) 
 template <class DT>
 __device__ __forceinline__ void stage_qkv(const DevModel& M, int layer, int wg, int nwg, float* smem) {
     const DevLayer& Ly = M.layers[layer];
-    compute_rstd(M, smem + kOffRstd);
-    EpiQKV<DT> epi{M, Ly, smem + kOffRstd, M.pp->L, M.pp->k};
+    EpiQKV<DT> epi{M, Ly, smem + kOffRstd, M.pp->L, M.pp->k, {}};
+    epi.pre.begin(M);
     gemm_stage<DT>(Ly.wqkv, M.nqkv / 16, M.d / DT::KB, M.A_hi, M.A_lo, M.d, M.pp->k, wg, nwg, epi, smem);
 }
 
@@ -370,8 +443,8 @@ __device__ __forceinline__ void stage_oproj(const DevModel& M, int layer, int wg
 template <class DT>
 __device__ __forceinline__ void stage_gateup(const DevModel& M, int layer, int wg, int nwg, float* smem) {
     const DevLayer& Ly = M.layers[layer];
-    compute_rstd(M, smem + kOffRstd);
-    EpiSwiGLU<DT> epi{M, smem + kOffRstd, M.pp->k};
+    EpiSwiGLU<DT> epi{M, smem + kOffRstd, M.pp->k, {}};
+    epi.pre.begin(M);
     gemm_stage<DT>(Ly.wgu, 2 * M.F / 16, M.d / DT::KB, M.A_hi, M.A_lo, M.d, M.pp->k, wg, nwg, epi, smem);
 }
 
@@ -385,8 +458,8 @@ __device__ __forceinline__ void stage_down(const DevModel& M, int layer, int wg,
 
 template <class DT>
 __device__ __forceinline__ void stage_lmhead(const DevModel& M, int wg, int nwg, float* smem) {
-    compute_rstd(M, smem + kOffRstd);
-    EpiLMHead epi{M, smem, M.pp->k, M.pp->keep_logits, -INFINITY, 0x7fffffff};
+    EpiLMHead epi{M, smem, M.pp->k, M.pp->keep_logits, -INFINITY, 0x7fffffff, {}};
+    epi.pre.begin(M);
     gemm_stage<DT>(M.wlm, M.V / 16, M.d / DT::KB, M.A_hi, M.A_lo, M.d, M.pp->k, wg, nwg, epi, smem);
     if (threadIdx.x < kRows && wg < M.lm_wgs) {
         M.best_val[wg * kRows + threadIdx.x] = epi.run_v;
@@ -395,20 +468,25 @@ __device__ __forceinline__ void stage_lmhead(const DevModel& M, int wg, int nwg,
 }
 
 // Causal grouped-query attention of the k rows against keys 0 .. L+k-1.
-// Work unit = (kv head, chunk of `chunk` consecutive key positions); wave w of
-// the workgroup takes key block w of the chunk (32 keys bf16 / 16 keys fp32),
-// loads its K and V fragments once and reuses them for the G query heads of
-// the group.  Scores are computed transposed (keys x rows) so that the
-// matrix-core result registers are, after the softmax numerator, already the
-// operand of the P.V product: no transposition through LDS.  Chunk and block
-// boundaries sit at fixed absolute positions, so a row's result does not depend
-// on how many rows the pass has or where the pass starts.
-// Output per (unit, head, row): running max, denominator, unnormalised numerator.
+// Work unit = (kv head, chunk of 8 key blocks; a block is 32 keys bf16 / 16 keys
+// fp32).  Wave w of the workgroup serves query head w % G of the group and the
+// w / G -th run of G consecutive blocks, walking them in order with a running
+// softmax (max, denominator, numerator) in registers; the next block's K and V
+// fragments are fetched while the current one is used.  Scores are computed
+// transposed (keys x rows) so that the matrix-core result registers are, after
+// the softmax numerator, already the operand of the P.V product: nothing is
+// transposed through LDS.  The 8/G runs of a head are merged through LDS in run
+// order.  Block, run and chunk boundaries sit at fixed absolute positions, so a
+// row's result does not depend on how many rows the pass has or where it starts.
+// Output per (unit, head, row): numerator[hd], running max, denominator.
+constexpr int kPartRow = 4;   // floats appended to a partial's numerator: max, denominator, 2 pad (keeps 16-byte alignment)
+
 template <class DT, int HD>
 __device__ __forceinline__ void stage_attention(const DevModel& M, int layer, int wg, int nwg, float* smem) {
     constexpr int FR = HD / 4 / DT::EPL;     // 16-byte fragments per lane along head_dim
     constexpr int HT = HD / 16;              // 16-wide head_dim tiles
     constexpr int BK = DT::BLOCK_KEYS, TPB = DT::TPB;
+    constexpr int HDP = HD + kAttPad;
     const DevLayer& Ly = M.layers[layer];
     const int L = M.pp->L, k = M.pp->k;
     const int T = L + k;
@@ -417,135 +495,149 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, int layer, in
     const int units = M.Hkv * nchunks;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
-    constexpr int HDP = HD + kAttPad;
-    float* partO = smem;                               // [wave][16][HD + pad]
-    float* partML = smem + kWaves * kRows * HDP;       // [wave][16][2]
+    const int G = M.G, parts = kWaves / G;
+    const int hq = wave % G, part = wave / G;
+    float* partO = smem;                               // [hq][part][16][HD + pad]
+    float* partML = smem + kWaves * kRows * HDP;       // [hq][part][16][2]
     const int nblk = M.ctx_pad / BK;
+    const uint4 zero4 = uint4{0, 0, 0, 0};
     for (int u = wg; u < units; u += nwg) {
         const int kvh = u / nchunks, c = u % nchunks;
-        const int p0 = c * CS + wave * BK;
-        const bool active = p0 < T;
+        const int head = kvh * G + hq;
+        const int b0 = c * kWaves + part * G;          // first block of this wave's run
+        uint4 qh[FR], ql[FR];
+        {
+            const int mq = m < k ? m : k - 1;          // rows >= k mirror row k-1; never written out
+            const size_t q0 = (size_t)mq * M.qdim + head * HD + g * (HD / 4);
+#pragma unroll
+            for (int i = 0; i < FR; ++i) {
+                qh[i] = load_frag<DT>(M.Q_hi, q0 + i * DT::EPL);
+                ql[i] = zero4;
+                if constexpr (DT::HAS_LO) ql[i] = load_frag<DT>(M.Q_lo, q0 + i * DT::EPL);
+            }
+        }
         uint4 kf[TPB][FR], vf[HT];
-        if (active) {
+        auto load_block = [&](int b, uint4 (&kd)[TPB][FR], uint4 (&vd)[HT]) {
+            const int bb = b < nblk ? b : nblk - 1;    // stay inside the cache allocation
 #pragma unroll
             for (int t = 0; t < TPB; ++t) {
-                const size_t e0 = ((size_t)kvh * M.ctx_pad + p0 + t * 16 + m) * HD + g * (HD / 4);
+                const size_t e0 = ((size_t)kvh * M.ctx_pad + bb * BK + t * 16 + m) * HD + g * (HD / 4);
 #pragma unroll
-                for (int i = 0; i < FR; ++i) kf[t][i] = load_frag<DT>(Ly.kcache, e0 + i * DT::EPL);
+                for (int i = 0; i < FR; ++i) kd[t][i] = load_frag<DT>(Ly.kcache, e0 + i * DT::EPL);
             }
-            const uint4* vb = reinterpret_cast<const uint4*>(Ly.vcache) + (((size_t)kvh * nblk + p0 / BK) * HT) * 64 + lane;
+            const uint4* vb = reinterpret_cast<const uint4*>(Ly.vcache) + (((size_t)kvh * nblk + bb) * HT) * 64 + lane;
 #pragma unroll
-            for (int j = 0; j < HT; ++j) vf[j] = vb[j * 64];
-        }
-        for (int hq = 0; hq < M.G; ++hq) {
-            const int head = kvh * M.G + hq;
-            float mx = -INFINITY, lsum = 0.f;
-            v4f o[HT];
+            for (int j = 0; j < HT; ++j) vd[j] = vb[j * 64];
+        };
+        load_block(b0, kf, vf);
+        float mrun = -INFINITY, lrun = 0.f;
+        v4f o[HT];
 #pragma unroll
-            for (int j = 0; j < HT; ++j) o[j] = v4f{0.f, 0.f, 0.f, 0.f};
-            if (active) {
-                uint4 qh[FR], ql[FR];
+        for (int j = 0; j < HT; ++j) o[j] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int ib = 0; ib < G; ++ib) {
+            const int p0 = (b0 + ib) * BK;
+            if (p0 >= T) break;                         // wave-uniform: later blocks of the run hold no visible key
+            uint4 kn[TPB][FR], vn[HT];
+            load_block(b0 + ib + 1, kn, vn);
+            float sv[TPB][4];
+            float mx = -INFINITY;
 #pragma unroll
-                for (int i = 0; i < FR; ++i) { qh[i] = uint4{0, 0, 0, 0}; ql[i] = uint4{0, 0, 0, 0}; }
-                if (m < k) {
-                    const size_t q0 = (size_t)m * M.qdim + head * HD + g * (HD / 4);
+            for (int t = 0; t < TPB; ++t) {
+                v4f sc = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int i = 0; i < FR; ++i) {
-                        qh[i] = load_frag<DT>(M.Q_hi, q0 + i * DT::EPL);
-                        if constexpr (DT::HAS_LO) ql[i] = load_frag<DT>(M.Q_lo, q0 + i * DT::EPL);
-                    }
+                for (int i = 0; i < FR; ++i) {
+                    sc = DT::mfma(kf[t][i], qh[i], sc);
+                    if constexpr (DT::HAS_LO) sc = DT::mfma(kf[t][i], ql[i], sc);
                 }
-                float sv[TPB][4];
 #pragma unroll
-                for (int t = 0; t < TPB; ++t) {
-                    v4f s = v4f{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int i = 0; i < FR; ++i) {
-                        s = DT::mfma(kf[t][i], qh[i], s);
-                        if constexpr (DT::HAS_LO) s = DT::mfma(kf[t][i], ql[i], s);
-                    }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int key = p0 + t * 16 + g * 4 + e;
-                        sv[t][e] = key <= L + m ? s[e] * M.att_scale : -INFINITY;   // causal: row m sees keys 0..L+m
-                        mx = fmaxf(mx, sv[t][e]);
-                    }
+                for (int e = 0; e < 4; ++e) {
+                    const int key = p0 + t * 16 + g * 4 + e;
+                    sv[t][e] = key <= L + m ? sc[e] * M.att_scale : -INFINITY;   // causal: row m sees keys 0..L+m
+                    mx = fmaxf(mx, sv[t][e]);
                 }
-                mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-                const float mref = mx == -INFINITY ? 0.f : mx;
-                float pv[TPB][4];
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float mnew = fmaxf(mrun, mx);
+            const float mref = mnew == -INFINITY ? 0.f : mnew;
+            const float alpha = __expf(mrun - mref);     // 0 for the first visible block
+            float pv[TPB][4], lsum = 0.f;
+#pragma unroll
+            for (int t = 0; t < TPB; ++t)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    pv[t][e] = __expf(sv[t][e] - mref);
+                    lsum += pv[t][e];
+                }
+            lsum = wave_xor_add(lsum, 16);
+            lsum = wave_xor_add(lsum, 32);
+            lrun = lrun * alpha + lsum;
+            mrun = mnew;
+            uint4 ph, pl = zero4;
+            if constexpr (DT::HAS_LO) {
+                uint32_t h[8], l[8];
 #pragma unroll
                 for (int t = 0; t < TPB; ++t)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        pv[t][e] = __expf(sv[t][e] - mref);
-                        lsum += pv[t][e];
+                        h[t * 4 + e] = bf16_rne(pv[t][e]);
+                        l[t * 4 + e] = bf16_rne(pv[t][e] - bf16_to_f32(h[t * 4 + e]));
                     }
-                lsum = wave_xor_add(lsum, 16);
-                lsum = wave_xor_add(lsum, 32);
-                uint4 ph, pl = uint4{0, 0, 0, 0};
-                if constexpr (DT::HAS_LO) {
-                    uint32_t h[8], l[8];
-#pragma unroll
-                    for (int t = 0; t < TPB; ++t)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            h[t * 4 + e] = bf16_rne(pv[t][e]);
-                            l[t * 4 + e] = bf16_rne(pv[t][e] - bf16_to_f32(h[t * 4 + e]));
-                        }
-                    ph = uint4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
-                    pl = uint4{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
-                } else {
-                    ph = uint4{__float_as_uint(pv[0][0]), __float_as_uint(pv[0][1]), __float_as_uint(pv[0][2]), __float_as_uint(pv[0][3])};
-                }
-#pragma unroll
-                for (int j = 0; j < HT; ++j) {
-                    o[j] = DT::mfma(vf[j], ph, o[j]);
-                    if constexpr (DT::HAS_LO) o[j] = DT::mfma(vf[j], pl, o[j]);
-                }
+                ph = uint4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+                pl = uint4{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+            } else {
+                ph = uint4{__float_as_uint(pv[0][0]), __float_as_uint(pv[0][1]), __float_as_uint(pv[0][2]), __float_as_uint(pv[0][3])};
             }
-            // wave partial to LDS: o[j][e] is head_dim index 16j + 4g + e of row m
 #pragma unroll
-            for (int j = 0; j < HT; ++j)
-                *reinterpret_cast<v4f*>(partO + ((size_t)(wave * kRows + m) * HDP + j * 16 + g * 4)) = o[j];
-            if (g == 0) {
-                partML[(wave * kRows + m) * 2 + 0] = mx;
-                partML[(wave * kRows + m) * 2 + 1] = lsum;
+            for (int j = 0; j < HT; ++j) {
+                o[j] = o[j] * alpha;
+                o[j] = DT::mfma(vf[j], ph, o[j]);
+                if constexpr (DT::HAS_LO) o[j] = DT::mfma(vf[j], pl, o[j]);
             }
-            __syncthreads();
-            // merge the 8 wave partials in wave order: thread = (row, slice of head_dim)
-            {
-                constexpr int PER = HD / 32;
-                const int mm = tid >> 5, c0 = (tid & 31) * PER;
-                if (mm < k) {
-                    float Mx = -INFINITY;
 #pragma unroll
-                    for (int w = 0; w < kWaves; ++w) Mx = fmaxf(Mx, partML[(w * kRows + mm) * 2]);
-                    float den = 0.f, num[PER];
+            for (int t = 0; t < TPB; ++t)
 #pragma unroll
-                    for (int x = 0; x < PER; ++x) num[x] = 0.f;
+                for (int i = 0; i < FR; ++i) kf[t][i] = kn[t][i];
 #pragma unroll
-                    for (int w = 0; w < kWaves; ++w) {
-                        const float mw = partML[(w * kRows + mm) * 2];
-                        const float wt = mw == -INFINITY ? 0.f : __expf(mw - Mx);
-                        den += wt * partML[(w * kRows + mm) * 2 + 1];
-#pragma unroll
-                        for (int x = 0; x < PER; ++x) num[x] += wt * partO[(size_t)(w * kRows + mm) * HDP + c0 + x];
-                    }
-                    float* out = M.att_part + (((size_t)u * M.G + hq) * kRows + mm) * (HD + 2);
-                    if ((tid & 31) == 0) { out[0] = Mx; out[1] = den; }
-#pragma unroll
-                    for (int x = 0; x < PER; ++x) out[2 + c0 + x] = num[x];
-                }
-            }
-            __syncthreads();
+            for (int j = 0; j < HT; ++j) vf[j] = vn[j];
         }
+        // run partial to LDS: o[j][e] is head_dim index 16j + 4g + e of row m
+        const int slot = hq * parts + part;
+#pragma unroll
+        for (int j = 0; j < HT; ++j)
+            *reinterpret_cast<v4f*>(partO + ((size_t)(slot * kRows + m) * HDP + j * 16 + g * 4)) = o[j];
+        if (g == 0) {
+            partML[(slot * kRows + m) * 2 + 0] = mrun;
+            partML[(slot * kRows + m) * 2 + 1] = lrun;
+        }
+        __syncthreads();
+        // merge the runs of each head in run order; item = (head, row, 4 consecutive head_dim entries)
+        for (int x = tid; x < G * kRows * (HD / 4); x += kThreads) {
+            const int c4 = x % (HD / 4), mm = (x / (HD / 4)) % kRows, hh = x / (kRows * (HD / 4));
+            if (mm >= k) continue;
+            float Mx = -INFINITY;
+            for (int pp = 0; pp < parts; ++pp) Mx = fmaxf(Mx, partML[((hh * parts + pp) * kRows + mm) * 2]);
+            float den = 0.f;
+            v4f num = v4f{0.f, 0.f, 0.f, 0.f};
+            for (int pp = 0; pp < parts; ++pp) {
+                const int sl = hh * parts + pp;
+                const float mw = partML[(sl * kRows + mm) * 2];
+                const float wt = mw == -INFINITY ? 0.f : __expf(mw - Mx);
+                den += wt * partML[(sl * kRows + mm) * 2 + 1];
+                num += wt * *reinterpret_cast<const v4f*>(partO + ((size_t)(sl * kRows + mm) * HDP + c4 * 4));
+            }
+            float* out = M.att_part + (((size_t)u * G + hh) * kRows + mm) * (HD + kPartRow);
+            *reinterpret_cast<v4f*>(out + c4 * 4) = num;
+            if (c4 == 0) { out[HD] = Mx; out[HD + 1] = den; }
+        }
+        __syncthreads();
     }
 }
 
 // Merge of the chunk partials of each (head, row) in chunk order -> normalised
-// attention output as the O-projection's input.  One wave per (head, row).
+// attention output as the O-projection's input.  One wave per (head, row):
+// lanes first hold one chunk each (max, weight, denominator), then one slice of
+// head_dim each.
 template <class DT, int HD>
 __device__ __forceinline__ void stage_attn_merge(const DevModel& M, int wg, int nwg) {
     const int L = M.pp->L, k = M.pp->k;
@@ -553,24 +645,42 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, int wg, int 
     const int nchunks = (T + CS - 1) / CS;
     const int lane = threadIdx.x & 63;
     const int gw = wg * kWaves + (threadIdx.x >> 6), nw = nwg * kWaves;
-    constexpr int PER = HD / 64;
+    constexpr int PER = HD / 64, ROW = HD + kPartRow;
     for (int x = gw; x < M.Hq * k; x += nw) {
         const int head = x / k, mm = x % k;
         const int kvh = head / M.G, hq = head % M.G;
         const int nch = (L + mm) / CS + 1;            // chunks holding keys this row can see
-        float Mx = -INFINITY;
-        for (int c = 0; c < nch; ++c)
-            Mx = fmaxf(Mx, M.att_part[((((size_t)kvh * nchunks + c) * M.G + hq) * kRows + mm) * (HD + 2)]);
-        float den = 0.f, num[PER];
+        const float* base = M.att_part + (((size_t)kvh * nchunks * M.G + hq) * kRows + mm) * ROW;
+        const size_t cstride = (size_t)M.G * kRows * ROW;
+        float Mrun = -INFINITY, den = 0.f, num[PER];
 #pragma unroll
         for (int i = 0; i < PER; ++i) num[i] = 0.f;
-        for (int c = 0; c < nch; ++c) {
-            const float* p = M.att_part + ((((size_t)kvh * nchunks + c) * M.G + hq) * kRows + mm) * (HD + 2);
-            const float mc = p[0];
-            const float wt = mc == -INFINITY ? 0.f : __expf(mc - Mx);
-            den += wt * p[1];
+        for (int c0 = 0; c0 < nch; c0 += 64) {        // groups of 64 chunks, in order
+            const int cc = c0 + lane;
+            const bool on = cc < nch;
+            const float* p = base + (size_t)(on ? cc : c0) * cstride;
+            const float mc = on ? p[HD] : -INFINITY;
+            const float dc = on ? p[HD + 1] : 0.f;
+            float Mg = mc;
 #pragma unroll
-            for (int i = 0; i < PER; ++i) num[i] += wt * p[2 + lane + 64 * i];
+            for (int off = 32; off >= 1; off >>= 1) Mg = fmaxf(Mg, __shfl_xor(Mg, off, 64));
+            const float Mnew = fmaxf(Mrun, Mg);       // finite: chunk 0 always holds key 0
+            const float scale_old = __expf(Mrun - Mnew);
+            const float wt = mc == -INFINITY ? 0.f : __expf(mc - Mnew);
+            float dsum = wt * dc;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) dsum += __shfl_xor(dsum, off, 64);
+            den = den * scale_old + dsum;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) num[i] *= scale_old;
+            const int ng = nch - c0 < 64 ? nch - c0 : 64;
+            for (int j = 0; j < ng; ++j) {
+                const float wj = __shfl(wt, j, 64);
+                const float* pj = base + (size_t)(c0 + j) * cstride;
+#pragma unroll
+                for (int i = 0; i < PER; ++i) num[i] += wj * pj[lane + 64 * i];
+            }
+            Mrun = Mnew;
         }
         const float inv = 1.0f / den;
 #pragma unroll
@@ -579,31 +689,34 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, int wg, int 
     }
 }
 
-// Arg-max across workgroups by wave shuffles, then the mismatch test of
-// Algorithm 1: target = [p_ctx, g[0], .., g[k-2]], accept the longest prefix
-// with draft == target, emit the model's own token at the first mismatch (or
-// g[k-1] when all match).  One wave.
-__device__ __forceinline__ void stage_accept(const DevModel& M) {
-    const int lane = threadIdx.x & 63;
+// Arg-max across workgroups by wave shuffles (wave r reduces row r), then the
+// mismatch test of Algorithm 1 on wave 0: target = [p_ctx, g[0], .., g[k-2]],
+// accept the longest prefix with draft == target, emit the model's own token at
+// the first mismatch (or g[k-1] when all match).  One workgroup of 16 waves.
+__device__ __forceinline__ void stage_accept(const DevModel& M, int* sg) {
+    const int lane = threadIdx.x & 63, row = threadIdx.x >> 6;
     const int k = M.pp->k;
-    int myg = -1;
-    for (int mm = 0; mm < k; ++mm) {
+    {
         float bv = -INFINITY;
         int bi = 0x7fffffff;
-        for (int w = lane; w < M.lm_wgs; w += 64) {
-            const float v = M.best_val[w * kRows + mm];
-            const int i = M.best_idx[w * kRows + mm];
-            if (better(v, i, bv, bi)) { bv = v; bi = i; }
-        }
+        if (row < k)
+            for (int w = lane; w < M.lm_wgs; w += 64) {
+                const float v = M.best_val[w * kRows + row];
+                const int i = M.best_idx[w * kRows + row];
+                if (better(v, i, bv, bi)) { bv = v; bi = i; }
+            }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
             const float ov = __shfl_xor(bv, off, 64);
             const int oi = __shfl_xor(bi, off, 64);
             if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
         }
-        if (lane == mm) myg = bi;
+        if (lane == 0) sg[row] = row < k ? bi : -1;
     }
-    if (lane < kRows) M.res->greedy[lane] = lane < k ? myg : -1;
+    __syncthreads();
+    if (row != 0) return;
+    const int myg = lane < kRows ? sg[lane] : -1;
+    if (lane < kRows) M.res->greedy[lane] = myg;
     // lane j holds g[j]; target[j] = j ? g[j-1] : p_ctx
     const int prev = __shfl_up(myg, 1, 64);
     const int target = lane == 0 ? M.pp->p_ctx : prev;
@@ -636,7 +749,10 @@ AMUSD_STAGE_KERNEL(k_gateup, (stage_gateup<DT>(M, layer, blockIdx.x, gridDim.x, 
 AMUSD_STAGE_KERNEL(k_down, (stage_down<DT>(M, layer, blockIdx.x, gridDim.x, smem)))
 AMUSD_STAGE_KERNEL(k_lmhead, (stage_lmhead<DT>(M, blockIdx.x, gridDim.x, smem)))
 
-__global__ void __launch_bounds__(64) k_accept(DevModel M) { stage_accept(M); }
+__global__ void __launch_bounds__(kRows * 64) k_accept(DevModel M) {
+    __shared__ int sg[kRows];
+    stage_accept(M, sg);
+}
 
 // ---------------------------------------------------------------- weight re-layout (model load)
 template <class DT>
@@ -710,27 +826,42 @@ hipError_t configure_kernels() {
 }
 
 template <class DT, int HD>
-static hipError_t launch_pass_t(const DevModel& M, int nwg, hipStream_t s) {
+static hipError_t launch_pass_t(const DevModel& M, int nwg, hipStream_t s, StageTimer* tm) {
     const dim3 blk(kThreads);
     const int embed_wgs = (M.d / 16 + 3) / 4 < nwg ? (M.d / 16 + 3) / 4 : nwg;
-    hipLaunchKernelGGL((k_embed<DT, HD>), dim3(embed_wgs), blk, 0, s, M, 0);
+    if (tm) tm->used = 0;
+    auto mark = [&](int stage, bool begin) {
+        if (tm && tm->stage == stage) {
+            (void)hipEventRecord(begin ? tm->begin[tm->used] : tm->end[tm->used], s);
+            if (!begin) ++tm->used;
+        }
+    };
+#define AMUSD_LAUNCH(stage, kern, grid, smem, arg)                              \
+    mark(stage, true);                                                           \
+    hipLaunchKernelGGL((kern<DT, HD>), dim3(grid), blk, smem, s, M, arg);       \
+    mark(stage, false);
+    AMUSD_LAUNCH(0, k_embed, embed_wgs, 0, 0)
     for (int l = 0; l < M.n_layers; ++l) {
-        hipLaunchKernelGGL((k_qkv<DT, HD>), dim3(nwg), blk, kSmemBytes, s, M, l);
-        hipLaunchKernelGGL((k_attention<DT, HD>), dim3(nwg), blk, kSmemBytes, s, M, l);
-        hipLaunchKernelGGL((k_attn_merge<DT, HD>), dim3(nwg), blk, 0, s, M, l);
-        hipLaunchKernelGGL((k_oproj<DT, HD>), dim3(nwg), blk, kSmemBytes, s, M, l);
-        hipLaunchKernelGGL((k_gateup<DT, HD>), dim3(nwg), blk, kSmemBytes, s, M, l);
-        hipLaunchKernelGGL((k_down<DT, HD>), dim3(nwg), blk, kSmemBytes, s, M, l);
+        AMUSD_LAUNCH(1, k_qkv, nwg, kSmemBytes, l)
+        AMUSD_LAUNCH(2, k_attention, nwg, kSmemBytes, l)
+        AMUSD_LAUNCH(3, k_attn_merge, nwg, 0, l)
+        AMUSD_LAUNCH(4, k_oproj, nwg, kSmemBytes, l)
+        AMUSD_LAUNCH(5, k_gateup, nwg, kSmemBytes, l)
+        AMUSD_LAUNCH(6, k_down, nwg, kSmemBytes, l)
     }
-    hipLaunchKernelGGL((k_lmhead<DT, HD>), dim3(M.lm_wgs), blk, kSmemBytes, s, M, 0);
-    hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, s, M);
+    AMUSD_LAUNCH(7, k_lmhead, M.lm_wgs, kSmemBytes, 0)
+#undef AMUSD_LAUNCH
+    mark(8, true);
+    hipLaunchKernelGGL(k_accept, dim3(1), dim3(kRows * 64), 0, s, M);
+    mark(8, false);
     return hipGetLastError();
 }
 
-hipError_t launch_pass(const DevModel& M, int nwg, hipStream_t stream, bool single_kernel) {
+hipError_t launch_pass(const DevModel& M, int nwg, hipStream_t stream, bool single_kernel, StageTimer* tm) {
     (void)single_kernel;
-    if (M.dtype) return M.hd == 128 ? launch_pass_t<BF16, 128>(M, nwg, stream) : launch_pass_t<BF16, 64>(M, nwg, stream);
-    return M.hd == 128 ? launch_pass_t<FP32, 128>(M, nwg, stream) : launch_pass_t<FP32, 64>(M, nwg, stream);
+    if (M.dtype)
+        return M.hd == 128 ? launch_pass_t<BF16, 128>(M, nwg, stream, tm) : launch_pass_t<BF16, 64>(M, nwg, stream, tm);
+    return M.hd == 128 ? launch_pass_t<FP32, 128>(M, nwg, stream, tm) : launch_pass_t<FP32, 64>(M, nwg, stream, tm);
 }
 
 }  // namespace amusd

@@ -19,7 +19,15 @@ hipError_t configure_kernels();
 hipError_t launch_relayout(int dtype, uint4* dst, const void* src, int K, int n_tiles, int tile_offset, int kind,
                            int hd, hipStream_t stream);
 
+// Optional bracketing of one stage's launches with events (one pair per launch).
+struct StageTimer {
+    int stage = -1;
+    hipEvent_t* begin = nullptr;   // [n_layers]
+    hipEvent_t* end = nullptr;
+    int used = 0;                  // pairs recorded by the last launch_pass
+};
+
 // Enqueues one whole pass (all stages) on the stream.
-hipError_t launch_pass(const DevModel& M, int nwg, hipStream_t stream, bool single_kernel);
+hipError_t launch_pass(const DevModel& M, int nwg, hipStream_t stream, bool single_kernel, StageTimer* timer);
 
 }  // namespace amusd
