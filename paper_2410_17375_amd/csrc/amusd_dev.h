@@ -11,15 +11,15 @@ constexpr int kWaves = 8;          // waves per workgroup
 constexpr int kThreads = kWaves * 64;
 constexpr int kMaxTilesPerRound = 8;
 
-// Values that change from pass to pass live in device memory so that a
-// captured launch sequence can be replayed unchanged.
-struct PassParams {
+// Per-pass values.  They travel as kernel arguments (no device round trip
+// before the first weight load can be addressed).
+struct PassArgs {
     int L;             // cache length before the pass (ctx_len)
     int k;             // rows
     int force_accept;  // 1: prefill, every row is kept
     int keep_logits;   // 1: store fp32 logits
     int p_ctx;         // model's greedy token for position L
-    int pad[3];
+    int tokens[kRows]; // input token of each row
 };
 
 struct PassResult {
@@ -45,7 +45,8 @@ struct DevModel {
     int qdim, kvdim, nqkv;
     int max_ctx, ctx_pad;
     int dtype;
-    int chunk;            // keys per attention work unit (waves x keys-per-block)
+    int chunk;            // keys per attention work unit: (8/G) runs x bpw blocks x keys-per-block
+    int bpw;              // key blocks a wave walks in one attention work unit
     int max_chunks;
     int lm_wgs;           // workgroups that produce arg-max partials
     float eps, att_scale;
@@ -56,21 +57,16 @@ struct DevModel {
     const float* rope_cos;   // [ctx_pad][hd/2]
     const float* rope_sin;
     float* X;             // residual stream [16][d]
-    void* A_hi;           // GEMM input, gain applied, not yet divided by the RMS: [16][d] (bf16 hi part, or fp32)
-    void* A_lo;           // bf16 lo part
+    void* A;              // norm-fed GEMM input (gain applied, not yet divided by the RMS), operand order, d columns
     float* ssq;           // [d/16][16] partial sums of squares of X rows
     void* Q_hi;           // [16][qdim]
     void* Q_lo;
     float* att_part;      // [units][G][16][hd+4]: numerator[hd], max, denominator, 2 pad
-    void* O_hi;           // merged attention output [16][qdim]
-    void* O_lo;
-    void* H_hi;           // SwiGLU output [16][F]
-    void* H_lo;
+    void* O;              // merged attention output, operand order, qdim columns
+    void* H;              // SwiGLU output, operand order, F columns
     float* logits;        // [16][V]
     float* best_val;      // [lm_wgs][16]
     int* best_idx;
-    const int* tokens;    // [16]
-    const PassParams* pp;
     PassResult* res;
     unsigned* barrier;    // grid barrier state (single-kernel mode)
 };

@@ -36,15 +36,8 @@ int fail(int code, const std::string& msg) {
             return fail(AMUSD_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));                \
     } while (0)
 
-struct HostStage {          // pinned: what one pass sends to and receives from the device
-    int tokens[kRows];
-    PassParams pp;
+struct HostStage {          // pinned: what one pass receives from the device
     PassResult res;
-};
-
-struct DevStage {           // device mirror of the inputs
-    int tokens[kRows];
-    PassParams pp;
 };
 
 }  // namespace
@@ -66,7 +59,6 @@ struct amusd_model {
     std::vector<void*> allocs;             // everything to hipFree
     std::vector<DevLayer> layers_host;
     DevModel dm{};
-    DevStage* dstage = nullptr;
     HostStage* hstage = nullptr;
     void* staging = nullptr;               // device staging for host-provided tensors
     size_t staging_bytes = 0;
@@ -154,15 +146,16 @@ hipError_t g_cfg_err = hipSuccess;
 // Runs one pass of `k` rows at cache length L.  Tokens already validated.
 int run_pass(amusd_model* m, int L, const int32_t* tokens, int k, bool force_accept) {
     HostStage* h = m->hstage;
-    for (int j = 0; j < kRows; ++j) h->tokens[j] = j < k ? tokens[j] : 0;
-    h->pp.L = L;
-    h->pp.k = k;
-    h->pp.force_accept = force_accept ? 1 : 0;
-    h->pp.keep_logits = m->keep_logits ? 1 : 0;
-    h->pp.p_ctx = m->greedy_at[L];
+    PassArgs P;
+    for (int j = 0; j < kRows; ++j) P.tokens[j] = j < k ? tokens[j] : 0;
+    P.L = L;
+    P.k = k;
+    P.force_accept = force_accept ? 1 : 0;
+    P.keep_logits = m->keep_logits ? 1 : 0;
+    P.p_ctx = m->greedy_at[L];
     HIP_TRY(hipEventRecord(m->ev0, m->stream));
-    HIP_TRY(hipMemcpyAsync(m->dstage, h, sizeof(DevStage), hipMemcpyHostToDevice, m->stream));
-    HIP_TRY(launch_pass(m->dm, m->nwg, m->stream, m->single_kernel, m->timer.stage >= 0 ? &m->timer : nullptr));
+    HIP_TRY(launch_pass(m->dm, m->layers_host.data(), P, m->nwg, m->stream, m->single_kernel,
+                        m->timer.stage >= 0 ? &m->timer : nullptr));
     HIP_TRY(hipMemcpyAsync(&h->res, m->dm.res, sizeof(PassResult), hipMemcpyDeviceToHost, m->stream));
     HIP_TRY(hipEventRecord(m->ev1, m->stream));
     HIP_TRY(hipStreamSynchronize(m->stream));
@@ -248,7 +241,15 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
     D.F = c.d_ffn; D.V = c.vocab; D.G = c.n_q_heads / c.n_kv_heads;
     D.qdim = c.n_q_heads * c.head_dim; D.kvdim = c.n_kv_heads * c.head_dim; D.nqkv = D.qdim + 2 * D.kvdim;
     D.dtype = c.dtype;
-    D.chunk = kWaves * BK;
+    {   // attention work units: about one per CU at full context, each wave walking bpw key blocks
+        const int parts = kWaves / D.G;
+        const int per_kvh = m->nwg / D.Hkv > 0 ? m->nwg / D.Hkv : 1;
+        const long unit_min = (long)parts * BK;
+        long bpw = (c.max_ctx + per_kvh * unit_min - 1) / (per_kvh * unit_min);
+        if (bpw < 1) bpw = 1;
+        D.bpw = (int)bpw;
+        D.chunk = (int)(parts * bpw * BK);
+    }
     D.max_ctx = c.max_ctx;
     D.ctx_pad = (c.max_ctx + D.chunk - 1) / D.chunk * D.chunk;
     D.max_chunks = D.ctx_pad / D.chunk;
@@ -284,25 +285,19 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
     ALLOC(D.rope_cos, const float*, (size_t)D.ctx_pad * (D.hd / 2) * 4, false)
     ALLOC(D.rope_sin, const float*, (size_t)D.ctx_pad * (D.hd / 2) * 4, false)
     ALLOC(D.X, float*, kRows * d * 4, true)
-    ALLOC(D.A_hi, void*, kRows * d * 4, true)
-    ALLOC(D.A_lo, void*, kRows * d * 4, true)
+    ALLOC(D.A, void*, kRows * d * 4, true)
     ALLOC(D.ssq, float*, (d / 16) * kRows * 4, true)
     ALLOC(D.Q_hi, void*, kRows * q * 4, true)
     ALLOC(D.Q_lo, void*, kRows * q * 4, true)
     ALLOC(D.att_part, float*, (size_t)D.Hkv * D.max_chunks * D.G * kRows * (D.hd + 4) * 4, true)
-    ALLOC(D.O_hi, void*, kRows * q * 4, true)
-    ALLOC(D.O_lo, void*, kRows * q * 4, true)
-    ALLOC(D.H_hi, void*, kRows * F * 4, true)
-    ALLOC(D.H_lo, void*, kRows * F * 4, true)
+    ALLOC(D.O, void*, kRows * q * 4, true)
+    ALLOC(D.H, void*, kRows * F * 4, true)
     ALLOC(D.logits, float*, kRows * V * 4, true)
     ALLOC(D.best_val, float*, (size_t)m->nwg * kRows * 4, true)
     ALLOC(D.best_idx, int*, (size_t)m->nwg * kRows * 4, true)
     ALLOC(D.res, PassResult*, sizeof(PassResult), true)
     ALLOC(D.barrier, unsigned*, 256, true)
-    ALLOC(m->dstage, DevStage*, sizeof(DevStage), true)
 #undef ALLOC
-    D.tokens = m->dstage->tokens;
-    D.pp = &m->dstage->pp;
     if (hipMemcpyAsync(const_cast<DevLayer*>(D.layers), m->layers_host.data(), sizeof(DevLayer) * c.n_layers,
                        hipMemcpyHostToDevice, m->stream) != hipSuccess)
         return bail(fail(AMUSD_E_HIP, "layer table upload"));

@@ -73,6 +73,46 @@ __device__ __forceinline__ void store_act(void* hi, void* lo, size_t idx, float 
     }
 }
 
+// GEMM inputs are kept in matrix-core operand order, so that a wave fetches the
+// 16 rows x one K block it needs with ONE contiguous 1 KiB load, exactly like
+// a weight fragment: buf[kb][part][lane = g*16 + slot][EPL elements], where g
+// selects the lane group's EPL columns of the K block.
+//   fp32        : one part, slot = row.
+//   bf16, k <= 8: one part; slots 0-7 hold the hi halves of rows 0-7 and slots
+//                 8-15 their lo halves (x = hi + lo), so one MFMA yields W.hi in
+//                 result columns 0-7 and W.lo in columns 8-15;
+//   bf16, k > 8 : two parts (hi, lo), slot = row.
+// The two sums (W.hi and W.lo) are reduced separately and added at the end in
+// both bf16 forms, so a row's value does not depend on which form carried it.
+template <class DT>
+__device__ __forceinline__ void store_gemm_in(void* buf, int k_rows, int m, int col, float x) {
+    const int kb = col / DT::KB, g = (col % DT::KB) / DT::EPL, e = col % DT::EPL;
+    if constexpr (DT::HAS_LO) {
+        const uint32_t h = bf16_rne(x);
+        const uint32_t l = bf16_rne(x - bf16_to_f32(h));
+        uint16_t* b = reinterpret_cast<uint16_t*>(buf);
+        if (k_rows <= 8) {
+            const size_t base = ((size_t)kb * 64 + g * 16 + m) * 8 + e;
+            b[base] = (uint16_t)h;
+            b[base + 8 * 8] = (uint16_t)l;                 // slot m + 8
+        } else {
+            const size_t base = ((size_t)kb * 128 + g * 16 + m) * 8 + e;
+            b[base] = (uint16_t)h;
+            b[base + 64 * 8] = (uint16_t)l;                // part 1
+        }
+    } else {
+        reinterpret_cast<float*>(buf)[((size_t)kb * 64 + g * 16 + m) * 4 + e] = x;
+    }
+}
+
+// Weights are read once per pass: a non-temporal load keeps them from evicting
+// the (re-read) activations from L2.
+__device__ __forceinline__ uint4 load_stream(const uint4* p) {
+    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+    const u4 v = __builtin_nontemporal_load(reinterpret_cast<const u4*>(p));
+    return uint4{v.x, v.y, v.z, v.w};
+}
+
 template <class DT>
 __device__ __forceinline__ uint4 load_frag(const void* base, size_t elem_index) {
     return *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(base) + elem_index * DT::ESZ);
@@ -126,105 +166,129 @@ struct RstdPrefetch {
 // unconditional (out-of-range stages re-read the last stage and multiply by a
 // zeroed activation), so the loop body is straight-line code and the hardware
 // load queue stays D stages deep: with 8 waves per CU that is 64-128 KiB of
-// weight bytes in flight per CU, what it takes to cover HBM latency at 8 TB/s.
-template <class DT, int NT, int D>
+// weight bytes in flight per CU, what it takes to cover HBM latency.
+enum { kActSingle = 0, kActPacked8 = 1, kActHiLo = 2 };
+
+template <class DT, int MODE, int NT, int D>
 __device__ __forceinline__ void gemm_accumulate(v4f (&acc)[kMaxTilesPerRound], const uint4* __restrict__ W, int tile0,
                                                 int tile_stride, int kblocks, int kb0, int S,
-                                                const char* __restrict__ ah, const char* __restrict__ al, int lane) {
-    constexpr size_t ASTEP = (size_t)DT::KB * DT::ESZ;   // bytes of one K block of one activation row
+                                                const uint4* __restrict__ act, int lane) {
+    constexpr int AF = MODE == kActHiLo ? 2 : 1;          // activation fragments per K block
     const uint4* wp[NT];
 #pragma unroll
     for (int j = 0; j < NT; ++j) wp[j] = W + ((size_t)(tile0 + tile_stride * j) * kblocks + kb0) * 64 + lane;
-    uint4 wb[D][NT], bh[D], bl[D];
+    const uint4* ap = act + (size_t)kb0 * (AF * 64) + lane;
+    uint4 wb[D][NT], ab[D][AF];
     const int last = S - 1;
 #pragma unroll
     for (int i = 0; i < D; ++i) {
         const int s = i < last ? i : last;
 #pragma unroll
-        for (int j = 0; j < NT; ++j) wb[i][j] = wp[j][(size_t)s * 64];
-        bh[i] = *reinterpret_cast<const uint4*>(ah + s * ASTEP);
-        if constexpr (DT::HAS_LO) bl[i] = *reinterpret_cast<const uint4*>(al + s * ASTEP);
+        for (int j = 0; j < NT; ++j) wb[i][j] = load_stream(wp[j] + (size_t)s * 64);
+#pragma unroll
+        for (int f = 0; f < AF; ++f) ab[i][f] = ap[(size_t)s * (AF * 64) + f * 64];
     }
     int s0 = 0;
     for (; s0 + D < S; s0 += D) {
 #pragma unroll
         for (int i = 0; i < D; ++i) {
 #pragma unroll
-            for (int j = 0; j < NT; ++j) {
-                acc[j] = DT::mfma(wb[i][j], bh[i], acc[j]);
-                if constexpr (DT::HAS_LO) acc[j] = DT::mfma(wb[i][j], bl[i], acc[j]);
-            }
+            for (int j = 0; j < NT; ++j)
+#pragma unroll
+                for (int f = 0; f < AF; ++f) acc[j * AF + f] = DT::mfma(wb[i][j], ab[i][f], acc[j * AF + f]);
             const int sn = s0 + i + D < last ? s0 + i + D : last;
 #pragma unroll
-            for (int j = 0; j < NT; ++j) wb[i][j] = wp[j][(size_t)sn * 64];
-            bh[i] = *reinterpret_cast<const uint4*>(ah + sn * ASTEP);
-            if constexpr (DT::HAS_LO) bl[i] = *reinterpret_cast<const uint4*>(al + sn * ASTEP);
+            for (int j = 0; j < NT; ++j) wb[i][j] = load_stream(wp[j] + (size_t)sn * 64);
+#pragma unroll
+            for (int f = 0; f < AF; ++f) ab[i][f] = ap[(size_t)sn * (AF * 64) + f * 64];
         }
     }
 #pragma unroll
     for (int i = 0; i < D; ++i) {
         const bool on = s0 + i < S;
         const uint4 z = uint4{0, 0, 0, 0};
-        const uint4 h = on ? bh[i] : z;
 #pragma unroll
-        for (int j = 0; j < NT; ++j) {
-            acc[j] = DT::mfma(wb[i][j], h, acc[j]);
-            if constexpr (DT::HAS_LO) acc[j] = DT::mfma(wb[i][j], on ? bl[i] : z, acc[j]);
-        }
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int f = 0; f < AF; ++f) acc[j * AF + f] = DT::mfma(wb[i][j], on ? ab[i][f] : z, acc[j * AF + f]);
     }
 }
 
-template <class DT, class Epi>
-__device__ __forceinline__ void gemm_stage(const uint4* __restrict__ W, int n_tiles, int kblocks,
-                                           const void* __restrict__ Ahi, const void* __restrict__ Alo, int lda,
-                                           int k_rows, int wg, int nwg, Epi& epi, float* smem) {
-    constexpr int NTMAX = kMaxTilesPerRound;
+// MODE as above; in kActHiLo every tile has two accumulators, so a round holds
+// at most 4 tiles.
+template <class DT, int MODE, class Epi>
+__device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_tiles, int kblocks,
+                                             const void* __restrict__ A, int wg, int nwg, Epi& epi, float* smem) {
+    constexpr int SLOTS = kMaxTilesPerRound;                  // accumulator tiles per wave per round
+    constexpr int AF = MODE == kActHiLo ? 2 : 1;
+    constexpr int NTMAX = SLOTS / AF;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
     const int kb0 = (kblocks * wave) / kWaves, kb1 = (kblocks * (wave + 1)) / kWaves;
     const int S = kb1 - kb0;
     const int mine = wg < n_tiles ? (n_tiles - wg + nwg - 1) / nwg : 0;
-    // rows >= k re-read row k-1 (same cache lines, no extra traffic); their results are never used
-    const int mrow = m < k_rows ? m : k_rows - 1;
-    const size_t aoff = ((size_t)mrow * lda + (size_t)g * DT::EPL + (size_t)kb0 * DT::KB) * DT::ESZ;
-    const char* ah = reinterpret_cast<const char*>(Ahi) + aoff;
-    const char* al = reinterpret_cast<const char*>(Alo) + aoff;
+    const uint4* act = reinterpret_cast<const uint4*>(A);
     bool first = true;
     for (int i0 = 0; i0 < mine;) {
         const int left = mine - i0;
-        const int nt = left >= 8 ? 8 : left == 7 ? 7 : left >= 4 ? 4 : left >= 2 ? 2 : 1;
-        v4f acc[NTMAX];
+        int nt = left >= 8 ? 8 : left == 7 ? 7 : left >= 4 ? 4 : left >= 2 ? 2 : 1;
+        if (nt > NTMAX) nt = NTMAX;
+        const int t0 = wg + nwg * i0;
+        epi.prefetch(t0, nwg, nt);
+        v4f acc[SLOTS];
 #pragma unroll
-        for (int j = 0; j < NTMAX; ++j) acc[j] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < SLOTS; ++j) acc[j] = v4f{0.f, 0.f, 0.f, 0.f};
         if (S > 0) {
-            const int t0 = wg + nwg * i0;
-            switch (nt) {
-                case 8: gemm_accumulate<DT, 8, 2>(acc, W, t0, nwg, kblocks, kb0, S, ah, al, lane); break;
-                case 7: gemm_accumulate<DT, 7, 2>(acc, W, t0, nwg, kblocks, kb0, S, ah, al, lane); break;
-                case 4: gemm_accumulate<DT, 4, 4>(acc, W, t0, nwg, kblocks, kb0, S, ah, al, lane); break;
-                case 2: gemm_accumulate<DT, 2, 8>(acc, W, t0, nwg, kblocks, kb0, S, ah, al, lane); break;
-                default: gemm_accumulate<DT, 1, 8>(acc, W, t0, nwg, kblocks, kb0, S, ah, al, lane); break;
+            if constexpr (MODE == kActHiLo) {
+                switch (nt) {
+                    case 4: gemm_accumulate<DT, MODE, 4, 3>(acc, W, t0, nwg, kblocks, kb0, S, act, lane); break;
+                    case 2: gemm_accumulate<DT, MODE, 2, 6>(acc, W, t0, nwg, kblocks, kb0, S, act, lane); break;
+                    default: gemm_accumulate<DT, MODE, 1, 8>(acc, W, t0, nwg, kblocks, kb0, S, act, lane); break;
+                }
+            } else {
+                switch (nt) {
+                    case 8: gemm_accumulate<DT, MODE, 8, 2>(acc, W, t0, nwg, kblocks, kb0, S, act, lane); break;
+                    case 7: gemm_accumulate<DT, MODE, 7, 2>(acc, W, t0, nwg, kblocks, kb0, S, act, lane); break;
+                    case 4: gemm_accumulate<DT, MODE, 4, 4>(acc, W, t0, nwg, kblocks, kb0, S, act, lane); break;
+                    case 2: gemm_accumulate<DT, MODE, 2, 8>(acc, W, t0, nwg, kblocks, kb0, S, act, lane); break;
+                    default: gemm_accumulate<DT, MODE, 1, 16>(acc, W, t0, nwg, kblocks, kb0, S, act, lane); break;
+                }
             }
         }
-        // partial tiles to LDS as [wave][tile][m][n]; lane holds n = 4g..4g+3 of row m
+        // partial tiles to LDS as [wave][slot][column m][n]; lane holds n = 4g..4g+3 of result column m
 #pragma unroll
-        for (int j = 0; j < NTMAX; ++j)
-            if (j < nt) *reinterpret_cast<v4f*>(smem + ((wave * NTMAX + j) * 256 + m * 16 + g * 4)) = acc[j];
+        for (int j = 0; j < SLOTS; ++j)
+            if (j < nt * AF) *reinterpret_cast<v4f*>(smem + ((wave * SLOTS + j) * 256 + m * 16 + g * 4)) = acc[j];
         if (first) epi.prepare();
         first = false;
         __syncthreads();
-        for (int item = tid; item < NTMAX * 128; item += kThreads) {
+#pragma unroll
+        for (int it = 0; it * kThreads < NTMAX * 128; ++it) {
+            const int item = tid + it * kThreads;
             const int j = item >> 7, mm = (item >> 3) & 15, r = item & 7;
-            const bool valid = j < nt;
+            const bool valid = j < nt && (MODE != kActPacked8 || mm < 8);
             float v1 = 0.f, v2 = 0.f;
             if (valid) {
+                // slot and result column of the W.hi sum, and of the W.lo sum where there is one
+                const int sh = MODE == kActHiLo ? 2 * j : j, ch = mm;
+                const int sl = MODE == kActHiLo ? 2 * j + 1 : j, cl = MODE == kActPacked8 ? mm + 8 : mm;
 #pragma unroll
                 for (int w = 0; w < kWaves; ++w) {
-                    v1 += smem[(w * NTMAX + j) * 256 + mm * 16 + r];
-                    v2 += smem[(w * NTMAX + j) * 256 + mm * 16 + r + 8];
+                    v1 += smem[(w * SLOTS + sh) * 256 + ch * 16 + r];
+                    v2 += smem[(w * SLOTS + sh) * 256 + ch * 16 + r + 8];
+                }
+                if constexpr (MODE != kActSingle) {
+                    float l1 = 0.f, l2 = 0.f;
+#pragma unroll
+                    for (int w = 0; w < kWaves; ++w) {
+                        l1 += smem[(w * SLOTS + sl) * 256 + cl * 16 + r];
+                        l2 += smem[(w * SLOTS + sl) * 256 + cl * 16 + r + 8];
+                    }
+                    v1 += l1;
+                    v2 += l2;
                 }
             }
-            epi.item(wg + nwg * (i0 + (valid ? j : 0)), j, mm, r, v1, v2, valid);
+            epi.item(t0 + nwg * (valid ? j : 0), j, it, mm, r, v1, v2, valid);
         }
         __syncthreads();
         epi.round_end(nt);
@@ -232,26 +296,52 @@ __device__ __forceinline__ void gemm_stage(const uint4* __restrict__ W, int n_ti
     }
 }
 
+template <class DT, class Epi>
+__device__ __forceinline__ void gemm_stage(const uint4* __restrict__ W, int n_tiles, int kblocks,
+                                           const void* __restrict__ A, int k_rows, int wg, int nwg, Epi& epi,
+                                           float* smem) {
+    if constexpr (!DT::HAS_LO) {
+        gemm_stage_m<DT, kActSingle>(W, n_tiles, kblocks, A, wg, nwg, epi, smem);
+    } else {
+        if (k_rows <= 8) gemm_stage_m<DT, kActPacked8>(W, n_tiles, kblocks, A, wg, nwg, epi, smem);
+        else gemm_stage_m<DT, kActHiLo>(W, n_tiles, kblocks, A, wg, nwg, epi, smem);
+    }
+}
+
 // ---------------------------------------------------------------- epilogues
-// Residual update for a pair of columns, then the next GEMM's input: x*gain
-// split into hi/lo, and the tile's partial sum of squares per row.
+// An epilogue sees every pair (column r, column r+8) of each finished tile:
+//   prefetch(t0, stride, nt)  before the contraction of a round (tiles t0 + stride*j, j < nt):
+//                             fetch what item() will need, so it is the oldest entry of the load queue;
+//   prepare()                 once, before the first round's items (may use LDS; a barrier follows);
+//   item(tile, slot, it, row, r, v1, v2, valid)  thread's it-th item of the round (it < 2);
+//   round_end(nt)             after the barrier that ends a round.
+
+// thread's it-th item of a round -> (tile slot j, row, column pair r)
+__device__ __forceinline__ void item_coords(int it, int& j, int& mm, int& r) {
+    const int item = threadIdx.x + it * kThreads;
+    j = item >> 7;
+    mm = (item >> 3) & 15;
+    r = item & 7;
+}
+
+// Residual update for a pair of columns, then the next GEMM's input x*gain
+// (in operand order) and the tile's partial sum of squares per row.
 template <class DT>
-__device__ __forceinline__ void residual_pair(const DevModel& M, const float* __restrict__ gain, int tile, int mm, int r,
-                                              float x1, float x2, int k_rows, bool valid) {
+__device__ __forceinline__ void residual_pair(const DevModel& M, float g1, float g2, int tile, int mm, int r, float x1,
+                                              float x2, int k_rows, bool on) {
     const int c1 = tile * 16 + r, c2 = c1 + 8;
     float sq = 0.f;
-    if (valid && mm < k_rows) {
-        const size_t i1 = (size_t)mm * M.d + c1, i2 = (size_t)mm * M.d + c2;
-        M.X[i1] = x1;
-        M.X[i2] = x2;
-        store_act<DT>(M.A_hi, M.A_lo, i1, x1 * gain[c1]);
-        store_act<DT>(M.A_hi, M.A_lo, i2, x2 * gain[c2]);
+    if (on) {
+        M.X[(size_t)mm * M.d + c1] = x1;
+        M.X[(size_t)mm * M.d + c2] = x2;
+        store_gemm_in<DT>(M.A, k_rows, mm, c1, x1 * g1);
+        store_gemm_in<DT>(M.A, k_rows, mm, c2, x2 * g2);
         sq = x1 * x1 + x2 * x2;
     }
     sq = wave_xor_add(sq, 1);
     sq = wave_xor_add(sq, 2);
     sq = wave_xor_add(sq, 4);
-    if (valid && r == 0) M.ssq[tile * kRows + mm] = sq;
+    if (on && r == 0) M.ssq[tile * kRows + mm] = sq;
 }
 
 template <class DT>
@@ -259,13 +349,25 @@ struct EpiResidual {   // O-projection and down-projection: X += C, feed the nex
     const DevModel& M;
     const float* gain_next;
     int k_rows;
-    __device__ __forceinline__ void item(int tile, int /*slot*/, int mm, int r, float v1, float v2, bool valid) {
-        float x1 = 0.f, x2 = 0.f;
-        if (valid && mm < k_rows) {
-            x1 = M.X[(size_t)mm * M.d + tile * 16 + r] + v1;
-            x2 = M.X[(size_t)mm * M.d + tile * 16 + r + 8] + v2;
+    float px1[2], px2[2], pg1[2], pg2[2];
+    __device__ __forceinline__ void prefetch(int t0, int stride, int nt) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            int j, mm, r;
+            item_coords(it, j, mm, r);
+            px1[it] = px2[it] = pg1[it] = pg2[it] = 0.f;
+            if (j < nt && mm < k_rows) {
+                const int c1 = (t0 + stride * j) * 16 + r;
+                px1[it] = M.X[(size_t)mm * M.d + c1];
+                px2[it] = M.X[(size_t)mm * M.d + c1 + 8];
+                pg1[it] = gain_next[c1];
+                pg2[it] = gain_next[c1 + 8];
+            }
         }
-        residual_pair<DT>(M, gain_next, tile, mm, r, x1, x2, k_rows, valid);
+    }
+    __device__ __forceinline__ void item(int tile, int /*slot*/, int it, int mm, int r, float v1, float v2, bool valid) {
+        const bool on = valid && mm < k_rows;
+        residual_pair<DT>(M, pg1[it], pg2[it], tile, mm, r, px1[it] + v1, px2[it] + v2, k_rows, on);
     }
     __device__ __forceinline__ void prepare() {}
     __device__ __forceinline__ void round_end(int) {}
@@ -278,20 +380,37 @@ struct EpiQKV {        // RMS scale, rotary embedding on (i, i+hd/2) pairs, Q to
     float* rstd;         // LDS
     int L, k_rows;
     RstdPrefetch pre;
+    float pc[2], ps[2];
+    __device__ __forceinline__ void prefetch(int t0, int stride, int nt) {
+        const int hd = M.hd, tph = hd / 16, rot_tiles = (M.qdim + M.kvdim) / 16;
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            int j, mm, r;
+            item_coords(it, j, mm, r);
+            pc[it] = 1.f;
+            ps[it] = 0.f;
+            const int tile = t0 + stride * j;
+            if (j < nt && mm < k_rows && tile < rot_tiles) {
+                const int i = (tile % tph) * 8 + r;           // q and k sections both start at a head boundary
+                pc[it] = M.rope_cos[(size_t)(L + mm) * (hd / 2) + i];
+                ps[it] = M.rope_sin[(size_t)(L + mm) * (hd / 2) + i];
+            }
+        }
+    }
     __device__ __forceinline__ void prepare() { pre.finish(M, rstd); }
-    __device__ __forceinline__ void item(int tile, int /*slot*/, int mm, int r, float v1, float v2, bool valid) {
+    __device__ __forceinline__ void item(int tile, int /*slot*/, int it, int mm, int r, float v1, float v2, bool valid) {
         if (!valid || mm >= k_rows) return;
         const int hd = M.hd, tph = hd / 16;
         const float sc = rstd[mm];
-        float x1 = v1 * sc, x2 = v2 * sc;
+        const float x1 = v1 * sc, x2 = v2 * sc;
         const int pos = L + mm;
         const int qt = M.qdim / 16, kt = M.kvdim / 16;
         if (tile < qt + kt) {
             const bool isq = tile < qt;
             const int tt = isq ? tile : tile - qt;
             const int head = tt / tph, i = (tt % tph) * 8 + r;
-            const float c = M.rope_cos[(size_t)pos * (hd / 2) + i], s = M.rope_sin[(size_t)pos * (hd / 2) + i];
-            const float y1 = x1 * c - x2 * s, y2 = x1 * s + x2 * c;
+            const float c = pc[it], sn = ps[it];
+            const float y1 = x1 * c - x2 * sn, y2 = x1 * sn + x2 * c;
             if (isq) {
                 const size_t o = (size_t)mm * M.qdim + head * hd + i;
                 store_act<DT>(M.Q_hi, M.Q_lo, o, y1);
@@ -333,13 +452,14 @@ struct EpiSwiGLU {     // tile rows 0-7 are gate features, 8-15 the matching up 
     float* rstd;
     int k_rows;
     RstdPrefetch pre;
+    __device__ __forceinline__ void prefetch(int, int, int) {}
     __device__ __forceinline__ void prepare() { pre.finish(M, rstd); }
-    __device__ __forceinline__ void item(int tile, int /*slot*/, int mm, int r, float v1, float v2, bool valid) {
+    __device__ __forceinline__ void item(int tile, int /*slot*/, int /*it*/, int mm, int r, float v1, float v2, bool valid) {
         if (!valid || mm >= k_rows) return;
         const float sc = rstd[mm];
         const float gate = v1 * sc, up = v2 * sc;
         const float h = gate / (1.0f + __expf(-gate)) * up;
-        store_act<DT>(M.H_hi, M.H_lo, (size_t)mm * M.F + tile * 8 + r, h);
+        store_gemm_in<DT>(M.H, k_rows, mm, tile * 8 + r, h);
     }
     __device__ __forceinline__ void round_end(int) {}
 };
@@ -362,8 +482,9 @@ struct EpiLMHead {     // logits (optionally stored); per-row arg-max over this 
     float run_v;         // thread mm < 16 keeps the workgroup's running best for row mm
     int run_i;
     RstdPrefetch pre;
+    __device__ __forceinline__ void prefetch(int, int, int) {}
     __device__ __forceinline__ void prepare() { pre.finish(M, smem + kOffRstd); }
-    __device__ __forceinline__ void item(int tile, int slot, int mm, int r, float v1, float v2, bool valid) {
+    __device__ __forceinline__ void item(int tile, int slot, int /*it*/, int mm, int r, float v1, float v2, bool valid) {
         const float sc = smem[kOffRstd + mm];
         const float z1 = v1 * sc, z2 = v2 * sc;
         const int c1 = tile * 16 + r, c2 = c1 + 8;
@@ -401,10 +522,10 @@ struct EpiLMHead {     // logits (optionally stored); per-row arg-max over this 
 // ---------------------------------------------------------------- stages
 // Embedding rows -> residual stream, first norm input, sums of squares.
 template <class DT>
-__device__ __forceinline__ void stage_embed(const DevModel& M, int wg, int nwg) {
-    const int k = M.pp->k;
+__device__ __forceinline__ void stage_embed(const DevModel& M, const float* __restrict__ gain, const PassArgs& P, int wg,
+                                            int nwg) {
+    const int k = P.k;
     const int ntiles = M.d / 16;
-    const float* gain = M.layers[0].g_attn;
     // 128 items per tile (16 rows x 8 column pairs); 4 tiles per sweep of the 512 threads
     const int sub = threadIdx.x >> 7, mm = (threadIdx.x >> 3) & 15, r = threadIdx.x & 7;
     for (int t0 = wg * 4; t0 < ntiles; t0 += nwg * 4) {
@@ -412,7 +533,7 @@ __device__ __forceinline__ void stage_embed(const DevModel& M, int wg, int nwg) 
         const bool valid = tile < ntiles;
         float x1 = 0.f, x2 = 0.f;
         if (valid && mm < k) {
-            const size_t o = (size_t)M.tokens[mm] * M.d + tile * 16 + r;
+            const size_t o = (size_t)P.tokens[mm] * M.d + tile * 16 + r;
             if constexpr (DT::HAS_LO) {
                 x1 = bf16_to_f32(reinterpret_cast<const uint16_t*>(M.embed)[o]);
                 x2 = bf16_to_f32(reinterpret_cast<const uint16_t*>(M.embed)[o + 8]);
@@ -421,46 +542,47 @@ __device__ __forceinline__ void stage_embed(const DevModel& M, int wg, int nwg) 
                 x2 = reinterpret_cast<const float*>(M.embed)[o + 8];
             }
         }
-        residual_pair<DT>(M, gain, valid ? tile : 0, mm, r, x1, x2, k, valid);
+        float g1 = 0.f, g2 = 0.f;
+        if (valid) { g1 = gain[tile * 16 + r]; g2 = gain[tile * 16 + r + 8]; }
+        residual_pair<DT>(M, g1, g2, valid ? tile : 0, mm, r, x1, x2, k, valid && mm < k);
     }
 }
 
 template <class DT>
-__device__ __forceinline__ void stage_qkv(const DevModel& M, int layer, int wg, int nwg, float* smem) {
-    const DevLayer& Ly = M.layers[layer];
-    EpiQKV<DT> epi{M, Ly, smem + kOffRstd, M.pp->L, M.pp->k, {}};
+__device__ __forceinline__ void stage_qkv(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int nwg,
+                                          float* smem) {
+    EpiQKV<DT> epi{M, Ly, smem + kOffRstd, P.L, P.k, {}, {}, {}};
     epi.pre.begin(M);
-    gemm_stage<DT>(Ly.wqkv, M.nqkv / 16, M.d / DT::KB, M.A_hi, M.A_lo, M.d, M.pp->k, wg, nwg, epi, smem);
+    gemm_stage<DT>(Ly.wqkv, M.nqkv / 16, M.d / DT::KB, M.A, P.k, wg, nwg, epi, smem);
 }
 
 template <class DT>
-__device__ __forceinline__ void stage_oproj(const DevModel& M, int layer, int wg, int nwg, float* smem) {
-    const DevLayer& Ly = M.layers[layer];
-    EpiResidual<DT> epi{M, Ly.g_mlp, M.pp->k};
-    gemm_stage<DT>(Ly.wo, M.d / 16, M.qdim / DT::KB, M.O_hi, M.O_lo, M.qdim, M.pp->k, wg, nwg, epi, smem);
+__device__ __forceinline__ void stage_oproj(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int nwg,
+                                            float* smem) {
+    EpiResidual<DT> epi{M, Ly.g_mlp, P.k, {}, {}, {}, {}};
+    gemm_stage<DT>(Ly.wo, M.d / 16, M.qdim / DT::KB, M.O, P.k, wg, nwg, epi, smem);
 }
 
 template <class DT>
-__device__ __forceinline__ void stage_gateup(const DevModel& M, int layer, int wg, int nwg, float* smem) {
-    const DevLayer& Ly = M.layers[layer];
-    EpiSwiGLU<DT> epi{M, smem + kOffRstd, M.pp->k, {}};
+__device__ __forceinline__ void stage_gateup(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int nwg,
+                                             float* smem) {
+    EpiSwiGLU<DT> epi{M, smem + kOffRstd, P.k, {}};
     epi.pre.begin(M);
-    gemm_stage<DT>(Ly.wgu, 2 * M.F / 16, M.d / DT::KB, M.A_hi, M.A_lo, M.d, M.pp->k, wg, nwg, epi, smem);
+    gemm_stage<DT>(Ly.wgu, 2 * M.F / 16, M.d / DT::KB, M.A, P.k, wg, nwg, epi, smem);
 }
 
 template <class DT>
-__device__ __forceinline__ void stage_down(const DevModel& M, int layer, int wg, int nwg, float* smem) {
-    const DevLayer& Ly = M.layers[layer];
-    const float* gain_next = layer + 1 < M.n_layers ? M.layers[layer + 1].g_attn : M.g_final;
-    EpiResidual<DT> epi{M, gain_next, M.pp->k};
-    gemm_stage<DT>(Ly.wd, M.d / 16, M.F / DT::KB, M.H_hi, M.H_lo, M.F, M.pp->k, wg, nwg, epi, smem);
+__device__ __forceinline__ void stage_down(const DevModel& M, const DevLayer& Ly, const float* gain_next,
+                                           const PassArgs& P, int wg, int nwg, float* smem) {
+    EpiResidual<DT> epi{M, gain_next, P.k, {}, {}, {}, {}};
+    gemm_stage<DT>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, nwg, epi, smem);
 }
 
 template <class DT>
-__device__ __forceinline__ void stage_lmhead(const DevModel& M, int wg, int nwg, float* smem) {
-    EpiLMHead epi{M, smem, M.pp->k, M.pp->keep_logits, -INFINITY, 0x7fffffff, {}};
+__device__ __forceinline__ void stage_lmhead(const DevModel& M, const PassArgs& P, int wg, int nwg, float* smem) {
+    EpiLMHead epi{M, smem, P.k, P.keep_logits, -INFINITY, 0x7fffffff, {}};
     epi.pre.begin(M);
-    gemm_stage<DT>(M.wlm, M.V / 16, M.d / DT::KB, M.A_hi, M.A_lo, M.d, M.pp->k, wg, nwg, epi, smem);
+    gemm_stage<DT>(M.wlm, M.V / 16, M.d / DT::KB, M.A, P.k, wg, nwg, epi, smem);
     if (threadIdx.x < kRows && wg < M.lm_wgs) {
         M.best_val[wg * kRows + threadIdx.x] = epi.run_v;
         M.best_idx[wg * kRows + threadIdx.x] = epi.run_i;
@@ -482,20 +604,20 @@ __device__ __forceinline__ void stage_lmhead(const DevModel& M, int wg, int nwg,
 constexpr int kPartRow = 4;   // floats appended to a partial's numerator: max, denominator, 2 pad (keeps 16-byte alignment)
 
 template <class DT, int HD>
-__device__ __forceinline__ void stage_attention(const DevModel& M, int layer, int wg, int nwg, float* smem) {
+__device__ __forceinline__ void stage_attention(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int nwg,
+                                                float* smem) {
     constexpr int FR = HD / 4 / DT::EPL;     // 16-byte fragments per lane along head_dim
     constexpr int HT = HD / 16;              // 16-wide head_dim tiles
     constexpr int BK = DT::BLOCK_KEYS, TPB = DT::TPB;
     constexpr int HDP = HD + kAttPad;
-    const DevLayer& Ly = M.layers[layer];
-    const int L = M.pp->L, k = M.pp->k;
+    const int L = P.L, k = P.k;
     const int T = L + k;
-    const int CS = M.chunk;                  // = kWaves * BK
+    const int CS = M.chunk;                  // = parts * bpw * BK
     const int nchunks = (T + CS - 1) / CS;
     const int units = M.Hkv * nchunks;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
-    const int G = M.G, parts = kWaves / G;
+    const int G = M.G, parts = kWaves / G, bpw = M.bpw;
     const int hq = wave % G, part = wave / G;
     float* partO = smem;                               // [hq][part][16][HD + pad]
     float* partML = smem + kWaves * kRows * HDP;       // [hq][part][16][2]
@@ -504,7 +626,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, int layer, in
     for (int u = wg; u < units; u += nwg) {
         const int kvh = u / nchunks, c = u % nchunks;
         const int head = kvh * G + hq;
-        const int b0 = c * kWaves + part * G;          // first block of this wave's run
+        const int b0 = (c * parts + part) * bpw;       // first block of this wave's run
         uint4 qh[FR], ql[FR];
         {
             const int mq = m < k ? m : k - 1;          // rows >= k mirror row k-1; never written out
@@ -534,7 +656,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, int layer, in
         v4f o[HT];
 #pragma unroll
         for (int j = 0; j < HT; ++j) o[j] = v4f{0.f, 0.f, 0.f, 0.f};
-        for (int ib = 0; ib < G; ++ib) {
+        for (int ib = 0; ib < bpw; ++ib) {
             const int p0 = (b0 + ib) * BK;
             if (p0 >= T) break;                         // wave-uniform: later blocks of the run hold no visible key
             uint4 kn[TPB][FR], vn[HT];
@@ -639,12 +761,13 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, int layer, in
 // lanes first hold one chunk each (max, weight, denominator), then one slice of
 // head_dim each.
 template <class DT, int HD>
-__device__ __forceinline__ void stage_attn_merge(const DevModel& M, int wg, int nwg) {
-    const int L = M.pp->L, k = M.pp->k;
+__device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassArgs& P, int wg, int nwg) {
+    const int L = P.L, k = P.k;
     const int T = L + k, CS = M.chunk;
     const int nchunks = (T + CS - 1) / CS;
     const int lane = threadIdx.x & 63;
-    const int gw = wg * kWaves + (threadIdx.x >> 6), nw = nwg * kWaves;
+    const int wpb = blockDim.x >> 6;
+    const int gw = wg * wpb + (threadIdx.x >> 6), nw = nwg * wpb;
     constexpr int PER = HD / 64, ROW = HD + kPartRow;
     for (int x = gw; x < M.Hq * k; x += nw) {
         const int head = x / k, mm = x % k;
@@ -685,7 +808,7 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, int wg, int 
         const float inv = 1.0f / den;
 #pragma unroll
         for (int i = 0; i < PER; ++i)
-            store_act<DT>(M.O_hi, M.O_lo, (size_t)mm * M.qdim + head * HD + lane + 64 * i, num[i] * inv);
+            store_gemm_in<DT>(M.O, k, mm, head * HD + lane + 64 * i, num[i] * inv);
     }
 }
 
@@ -693,9 +816,9 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, int wg, int 
 // mismatch test of Algorithm 1 on wave 0: target = [p_ctx, g[0], .., g[k-2]],
 // accept the longest prefix with draft == target, emit the model's own token at
 // the first mismatch (or g[k-1] when all match).  One workgroup of 16 waves.
-__device__ __forceinline__ void stage_accept(const DevModel& M, int* sg) {
+__device__ __forceinline__ void stage_accept(const DevModel& M, const PassArgs& P, int* sg) {
     const int lane = threadIdx.x & 63, row = threadIdx.x >> 6;
-    const int k = M.pp->k;
+    const int k = P.k;
     {
         float bv = -INFINITY;
         int bi = 0x7fffffff;
@@ -719,8 +842,8 @@ __device__ __forceinline__ void stage_accept(const DevModel& M, int* sg) {
     if (lane < kRows) M.res->greedy[lane] = myg;
     // lane j holds g[j]; target[j] = j ? g[j-1] : p_ctx
     const int prev = __shfl_up(myg, 1, 64);
-    const int target = lane == 0 ? M.pp->p_ctx : prev;
-    const bool match = lane < k && (M.pp->force_accept || M.tokens[lane] == target);
+    const int target = lane == 0 ? P.p_ctx : prev;
+    const bool match = lane < k && (P.force_accept || P.tokens[lane < kRows ? lane : 0] == target);
     const unsigned long long ball = __ballot(match);
     const int n = __ffsll((long long)~ball) - 1;          // first lane that does not match (lanes >= k never match)
     const int gk = __shfl(myg, k - 1, 64);
@@ -732,26 +855,26 @@ __device__ __forceinline__ void stage_accept(const DevModel& M, int* sg) {
 }
 
 // ---------------------------------------------------------------- one kernel per stage
-#define AMUSD_STAGE_KERNEL(name, body)                                                     \
-    template <class DT, int HD>                                                              \
-    __global__ void __launch_bounds__(kThreads) name(DevModel M, int layer) {               \
-        extern __shared__ float smem[];                                                      \
-        (void)layer; (void)smem;                                                             \
-        body;                                                                                \
+#define AMUSD_STAGE_KERNEL(name, body)                                                                     \
+    template <class DT, int HD>                                                                              \
+    __global__ void __launch_bounds__(kThreads) name(DevModel M, DevLayer Ly, const float* gain, PassArgs P) { \
+        extern __shared__ float smem[];                                                                      \
+        (void)smem; (void)gain; (void)Ly;                                                                    \
+        body;                                                                                                \
     }
 
-AMUSD_STAGE_KERNEL(k_embed, (stage_embed<DT>(M, blockIdx.x, gridDim.x)))
-AMUSD_STAGE_KERNEL(k_qkv, (stage_qkv<DT>(M, layer, blockIdx.x, gridDim.x, smem)))
-AMUSD_STAGE_KERNEL(k_attention, (stage_attention<DT, HD>(M, layer, blockIdx.x, gridDim.x, smem)))
-AMUSD_STAGE_KERNEL(k_attn_merge, (stage_attn_merge<DT, HD>(M, blockIdx.x, gridDim.x)))
-AMUSD_STAGE_KERNEL(k_oproj, (stage_oproj<DT>(M, layer, blockIdx.x, gridDim.x, smem)))
-AMUSD_STAGE_KERNEL(k_gateup, (stage_gateup<DT>(M, layer, blockIdx.x, gridDim.x, smem)))
-AMUSD_STAGE_KERNEL(k_down, (stage_down<DT>(M, layer, blockIdx.x, gridDim.x, smem)))
-AMUSD_STAGE_KERNEL(k_lmhead, (stage_lmhead<DT>(M, blockIdx.x, gridDim.x, smem)))
+AMUSD_STAGE_KERNEL(k_embed, (stage_embed<DT>(M, gain, P, blockIdx.x, gridDim.x)))
+AMUSD_STAGE_KERNEL(k_qkv, (stage_qkv<DT>(M, Ly, P, blockIdx.x, gridDim.x, smem)))
+AMUSD_STAGE_KERNEL(k_attention, (stage_attention<DT, HD>(M, Ly, P, blockIdx.x, gridDim.x, smem)))
+AMUSD_STAGE_KERNEL(k_attn_merge, (stage_attn_merge<DT, HD>(M, P, blockIdx.x, gridDim.x)))
+AMUSD_STAGE_KERNEL(k_oproj, (stage_oproj<DT>(M, Ly, P, blockIdx.x, gridDim.x, smem)))
+AMUSD_STAGE_KERNEL(k_gateup, (stage_gateup<DT>(M, Ly, P, blockIdx.x, gridDim.x, smem)))
+AMUSD_STAGE_KERNEL(k_down, (stage_down<DT>(M, Ly, gain, P, blockIdx.x, gridDim.x, smem)))
+AMUSD_STAGE_KERNEL(k_lmhead, (stage_lmhead<DT>(M, P, blockIdx.x, gridDim.x, smem)))
 
-__global__ void __launch_bounds__(kRows * 64) k_accept(DevModel M) {
+__global__ void __launch_bounds__(kRows * 64) k_accept(DevModel M, PassArgs P) {
     __shared__ int sg[kRows];
-    stage_accept(M, sg);
+    stage_accept(M, P, sg);
 }
 
 // ---------------------------------------------------------------- weight re-layout (model load)
@@ -826,9 +949,17 @@ hipError_t configure_kernels() {
 }
 
 template <class DT, int HD>
-static hipError_t launch_pass_t(const DevModel& M, int nwg, hipStream_t s, StageTimer* tm) {
+static hipError_t launch_pass_t(const DevModel& M, const DevLayer* Ls, const PassArgs& P, int nwg, hipStream_t s,
+                                StageTimer* tm) {
     const dim3 blk(kThreads);
     const int embed_wgs = (M.d / 16 + 3) / 4 < nwg ? (M.d / 16 + 3) / 4 : nwg;
+    const int T = P.L + P.k;
+    const int att_units = M.Hkv * ((T + M.chunk - 1) / M.chunk);
+    const int att_wgs = att_units < nwg ? att_units : nwg;
+    const int merge_wgs = M.Hq * P.k;      // one wave each
+    const int qkv_wgs = M.nqkv / 16 < nwg ? M.nqkv / 16 : nwg;
+    const int d_wgs = M.d / 16 < nwg ? M.d / 16 : nwg;
+    const int gu_wgs = 2 * M.F / 16 < nwg ? 2 * M.F / 16 : nwg;
     if (tm) tm->used = 0;
     auto mark = [&](int stage, bool begin) {
         if (tm && tm->stage == stage) {
@@ -836,32 +967,39 @@ static hipError_t launch_pass_t(const DevModel& M, int nwg, hipStream_t s, Stage
             if (!begin) ++tm->used;
         }
     };
-#define AMUSD_LAUNCH(stage, kern, grid, smem, arg)                              \
-    mark(stage, true);                                                           \
-    hipLaunchKernelGGL((kern<DT, HD>), dim3(grid), blk, smem, s, M, arg);       \
+    const float* nogain = nullptr;
+#define AMUSD_LAUNCH(stage, kern, grid, smem, layer, gain)                                  \
+    mark(stage, true);                                                                       \
+    hipLaunchKernelGGL((kern<DT, HD>), dim3(grid), blk, smem, s, M, Ls[layer], gain, P);    \
     mark(stage, false);
-    AMUSD_LAUNCH(0, k_embed, embed_wgs, 0, 0)
+    AMUSD_LAUNCH(0, k_embed, embed_wgs, 0, 0, Ls[0].g_attn)
     for (int l = 0; l < M.n_layers; ++l) {
-        AMUSD_LAUNCH(1, k_qkv, nwg, kSmemBytes, l)
-        AMUSD_LAUNCH(2, k_attention, nwg, kSmemBytes, l)
-        AMUSD_LAUNCH(3, k_attn_merge, nwg, 0, l)
-        AMUSD_LAUNCH(4, k_oproj, nwg, kSmemBytes, l)
-        AMUSD_LAUNCH(5, k_gateup, nwg, kSmemBytes, l)
-        AMUSD_LAUNCH(6, k_down, nwg, kSmemBytes, l)
+        const float* gain_next = l + 1 < M.n_layers ? Ls[l + 1].g_attn : M.g_final;
+        AMUSD_LAUNCH(1, k_qkv, qkv_wgs, kSmemBytes, l, nogain)
+        AMUSD_LAUNCH(2, k_attention, att_wgs, kSmemBytes, l, nogain)
+        mark(3, true);
+        hipLaunchKernelGGL((k_attn_merge<DT, HD>), dim3(merge_wgs), dim3(64), 0, s, M, Ls[l], nogain, P);
+        mark(3, false);
+        AMUSD_LAUNCH(4, k_oproj, d_wgs, kSmemBytes, l, nogain)
+        AMUSD_LAUNCH(5, k_gateup, gu_wgs, kSmemBytes, l, nogain)
+        AMUSD_LAUNCH(6, k_down, d_wgs, kSmemBytes, l, gain_next)
     }
-    AMUSD_LAUNCH(7, k_lmhead, M.lm_wgs, kSmemBytes, 0)
+    AMUSD_LAUNCH(7, k_lmhead, M.lm_wgs, kSmemBytes, 0, nogain)
 #undef AMUSD_LAUNCH
     mark(8, true);
-    hipLaunchKernelGGL(k_accept, dim3(1), dim3(kRows * 64), 0, s, M);
+    hipLaunchKernelGGL(k_accept, dim3(1), dim3(kRows * 64), 0, s, M, P);
     mark(8, false);
     return hipGetLastError();
 }
 
-hipError_t launch_pass(const DevModel& M, int nwg, hipStream_t stream, bool single_kernel, StageTimer* tm) {
+hipError_t launch_pass(const DevModel& M, const DevLayer* Ls, const PassArgs& P, int nwg, hipStream_t stream,
+                       bool single_kernel, StageTimer* tm) {
     (void)single_kernel;
     if (M.dtype)
-        return M.hd == 128 ? launch_pass_t<BF16, 128>(M, nwg, stream, tm) : launch_pass_t<BF16, 64>(M, nwg, stream, tm);
-    return M.hd == 128 ? launch_pass_t<FP32, 128>(M, nwg, stream, tm) : launch_pass_t<FP32, 64>(M, nwg, stream, tm);
+        return M.hd == 128 ? launch_pass_t<BF16, 128>(M, Ls, P, nwg, stream, tm)
+                           : launch_pass_t<BF16, 64>(M, Ls, P, nwg, stream, tm);
+    return M.hd == 128 ? launch_pass_t<FP32, 128>(M, Ls, P, nwg, stream, tm)
+                       : launch_pass_t<FP32, 64>(M, Ls, P, nwg, stream, tm);
 }
 
 }  // namespace amusd

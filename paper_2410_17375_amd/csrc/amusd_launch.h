@@ -28,6 +28,7 @@ struct StageTimer {
 };
 
 // Enqueues one whole pass (all stages) on the stream.
-hipError_t launch_pass(const DevModel& M, int nwg, hipStream_t stream, bool single_kernel, StageTimer* timer);
+hipError_t launch_pass(const DevModel& M, const DevLayer* layers_host, const PassArgs& P, int nwg, hipStream_t stream,
+                       bool single_kernel, StageTimer* timer);
 
 }  // namespace amusd
