@@ -5,7 +5,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libamusd.so")
+_LIB_PATH = os.environ.get("AMUSD_LIBRARY") or os.path.join(_HERE, "libamusd.so")
 
 DTYPE_FP32, DTYPE_BF16 = 0, 1
 MAX_K = 16

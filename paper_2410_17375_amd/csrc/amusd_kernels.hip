@@ -53,6 +53,18 @@ struct FP32 {
     }
 };
 
+#ifdef AMUSD_TRACE
+// Debug builds only: per-workgroup timestamps of the GEMM stages (wave 0).
+__device__ unsigned long long g_trace[8 * 256 * 8];
+__device__ unsigned long long g_trace_wave[8 * 256 * 8];   // [stage][wg][wave]: end of the wave's first contraction loop
+#define AMUSD_TP(stage, wg, idx)                                                                  \
+    do {                                                                                          \
+        if (threadIdx.x == 0 && (wg) < 256) g_trace[((stage) * 256 + (wg)) * 8 + (idx)] = wall_clock64(); \
+    } while (0)
+#else
+#define AMUSD_TP(stage, wg, idx) do { } while (0)
+#endif
+
 __device__ __forceinline__ uint32_t bf16_rne(float x) {
     uint32_t u = __float_as_uint(x);
     u += 0x7FFFu + ((u >> 16) & 1u);
@@ -168,6 +180,10 @@ struct RstdPrefetch {
 // load queue stays D stages deep: with 8 waves per CU that is 64-128 KiB of
 // weight bytes in flight per CU, what it takes to cover HBM latency.
 enum { kActSingle = 0, kActPacked8 = 1, kActHiLo = 2 };
+#ifndef AMUSD_OLD_SHARE
+#define AMUSD_OLD_SHARE 8
+#endif
+constexpr int kOldShare = AMUSD_OLD_SHARE;   // sixteenths of a SIMD's K range given to its first wave
 
 template <class DT, int MODE, int NT, int D>
 __device__ __forceinline__ void gemm_accumulate(v4f (&acc)[kMaxTilesPerRound], const uint4* __restrict__ W, int tile0,
@@ -224,17 +240,24 @@ __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_
     constexpr int NTMAX = SLOTS / AF;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
-    const int kb0 = (kblocks * wave) / kWaves, kb1 = (kblocks * (wave + 1)) / kWaves;
+    // K split: SIMD s hosts waves s and s+4; they share the K quarter of their SIMD.  The first wave of a
+    // SIMD wins the issue arbitration and streams faster, so it takes the larger share (kOldShare/16).
+    const int simd = wave & 3, young = wave >> 2;
+    const int q0 = (kblocks * simd) / 4, q1 = (kblocks * (simd + 1)) / 4;
+    const int cut = q0 + ((q1 - q0) * kOldShare + 8) / 16;
+    const int kb0 = young ? cut : q0, kb1 = young ? q1 : cut;
     const int S = kb1 - kb0;
     const int mine = wg < n_tiles ? (n_tiles - wg + nwg - 1) / nwg : 0;
     const uint4* act = reinterpret_cast<const uint4*>(A);
     bool first = true;
+    AMUSD_TP(Epi::kStage, wg, 0);
     for (int i0 = 0; i0 < mine;) {
         const int left = mine - i0;
         int nt = left >= 8 ? 8 : left == 7 ? 7 : left >= 4 ? 4 : left >= 2 ? 2 : 1;
         if (nt > NTMAX) nt = NTMAX;
         const int t0 = wg + nwg * i0;
         epi.prefetch(t0, nwg, nt);
+        if (first) AMUSD_TP(Epi::kStage, wg, 1);
         v4f acc[SLOTS];
 #pragma unroll
         for (int j = 0; j < SLOTS; ++j) acc[j] = v4f{0.f, 0.f, 0.f, 0.f};
@@ -259,9 +282,13 @@ __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_
 #pragma unroll
         for (int j = 0; j < SLOTS; ++j)
             if (j < nt * AF) *reinterpret_cast<v4f*>(smem + ((wave * SLOTS + j) * 256 + m * 16 + g * 4)) = acc[j];
+        if (first) AMUSD_TP(Epi::kStage, wg, 2);
+#ifdef AMUSD_TRACE
+        if (first && lane == 0 && wg < 256) g_trace_wave[(Epi::kStage * 256 + wg) * 8 + wave] = wall_clock64();
+#endif
         if (first) epi.prepare();
-        first = false;
         __syncthreads();
+        if (first) AMUSD_TP(Epi::kStage, wg, 3);
 #pragma unroll
         for (int it = 0; it * kThreads < NTMAX * 128; ++it) {
             const int item = tid + it * kThreads;
@@ -290,8 +317,11 @@ __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_
             }
             epi.item(t0 + nwg * (valid ? j : 0), j, it, mm, r, v1, v2, valid);
         }
+        if (first) AMUSD_TP(Epi::kStage, wg, 4);
         __syncthreads();
         epi.round_end(nt);
+        if (first) AMUSD_TP(Epi::kStage, wg, 5);
+        first = false;
         i0 += nt;
     }
 }
@@ -344,8 +374,9 @@ __device__ __forceinline__ void residual_pair(const DevModel& M, float g1, float
     if (on && r == 0) M.ssq[tile * kRows + mm] = sq;
 }
 
-template <class DT>
+template <class DT, int STAGE>
 struct EpiResidual {   // O-projection and down-projection: X += C, feed the next norm
+    static constexpr int kStage = STAGE;
     const DevModel& M;
     const float* gain_next;
     int k_rows;
@@ -374,7 +405,8 @@ struct EpiResidual {   // O-projection and down-projection: X += C, feed the nex
 };
 
 template <class DT>
-struct EpiQKV {        // RMS scale, rotary embedding on (i, i+hd/2) pairs, Q to its buffer, K/V appended to the cache
+struct EpiQKV {
+    static constexpr int kStage = 1;        // RMS scale, rotary embedding on (i, i+hd/2) pairs, Q to its buffer, K/V appended to the cache
     const DevModel& M;
     const DevLayer& Ly;
     float* rstd;         // LDS
@@ -448,6 +480,7 @@ struct EpiQKV {        // RMS scale, rotary embedding on (i, i+hd/2) pairs, Q to
 
 template <class DT>
 struct EpiSwiGLU {     // tile rows 0-7 are gate features, 8-15 the matching up features
+    static constexpr int kStage = 5;
     const DevModel& M;
     float* rstd;
     int k_rows;
@@ -475,7 +508,8 @@ constexpr int kSmemFloats = kOffTileBestI + kMaxTilesPerRound * kRows;
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 
-struct EpiLMHead {     // logits (optionally stored); per-row arg-max over this workgroup's tiles, lowest id on ties
+struct EpiLMHead {
+    static constexpr int kStage = 7;     // logits (optionally stored); per-row arg-max over this workgroup's tiles, lowest id on ties
     const DevModel& M;
     float* smem;
     int k_rows, keep;
@@ -559,7 +593,7 @@ __device__ __forceinline__ void stage_qkv(const DevModel& M, const DevLayer& Ly,
 template <class DT>
 __device__ __forceinline__ void stage_oproj(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int nwg,
                                             float* smem) {
-    EpiResidual<DT> epi{M, Ly.g_mlp, P.k, {}, {}, {}, {}};
+    EpiResidual<DT, 4> epi{M, Ly.g_mlp, P.k, {}, {}, {}, {}};
     gemm_stage<DT>(Ly.wo, M.d / 16, M.qdim / DT::KB, M.O, P.k, wg, nwg, epi, smem);
 }
 
@@ -574,7 +608,7 @@ __device__ __forceinline__ void stage_gateup(const DevModel& M, const DevLayer& 
 template <class DT>
 __device__ __forceinline__ void stage_down(const DevModel& M, const DevLayer& Ly, const float* gain_next,
                                            const PassArgs& P, int wg, int nwg, float* smem) {
-    EpiResidual<DT> epi{M, gain_next, P.k, {}, {}, {}, {}};
+    EpiResidual<DT, 6> epi{M, gain_next, P.k, {}, {}, {}, {}};
     gemm_stage<DT>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, nwg, epi, smem);
 }
 
@@ -623,6 +657,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
     float* partML = smem + kWaves * kRows * HDP;       // [hq][part][16][2]
     const int nblk = M.ctx_pad / BK;
     const uint4 zero4 = uint4{0, 0, 0, 0};
+    AMUSD_TP(2, wg, 0);
     for (int u = wg; u < units; u += nwg) {
         const int kvh = u / nchunks, c = u % nchunks;
         const int head = kvh * G + hq;
@@ -652,6 +687,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
             for (int j = 0; j < HT; ++j) vd[j] = vb[j * 64];
         };
         load_block(b0, kf, vf);
+        AMUSD_TP(2, wg, 1);
         float mrun = -INFINITY, lrun = 0.f;
         v4f o[HT];
 #pragma unroll
@@ -723,6 +759,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
 #pragma unroll
             for (int j = 0; j < HT; ++j) vf[j] = vn[j];
         }
+        AMUSD_TP(2, wg, 2);
         // run partial to LDS: o[j][e] is head_dim index 16j + 4g + e of row m
         const int slot = hq * parts + part;
 #pragma unroll
@@ -733,6 +770,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
             partML[(slot * kRows + m) * 2 + 1] = lrun;
         }
         __syncthreads();
+        AMUSD_TP(2, wg, 3);
         // merge the runs of each head in run order; item = (head, row, 4 consecutive head_dim entries)
         for (int x = tid; x < G * kRows * (HD / 4); x += kThreads) {
             const int c4 = x % (HD / 4), mm = (x / (HD / 4)) % kRows, hh = x / (kRows * (HD / 4));
@@ -752,7 +790,9 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
             *reinterpret_cast<v4f*>(out + c4 * 4) = num;
             if (c4 == 0) { out[HD] = Mx; out[HD + 1] = den; }
         }
+        AMUSD_TP(2, wg, 4);
         __syncthreads();
+        AMUSD_TP(2, wg, 5);
     }
 }
 
@@ -769,6 +809,7 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassAr
     const int wpb = blockDim.x >> 6;
     const int gw = wg * wpb + (threadIdx.x >> 6), nw = nwg * wpb;
     constexpr int PER = HD / 64, ROW = HD + kPartRow;
+    AMUSD_TP(3, wg, 0);
     for (int x = gw; x < M.Hq * k; x += nw) {
         const int head = x / k, mm = x % k;
         const int kvh = head / M.G, hq = head % M.G;
@@ -809,6 +850,7 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassAr
 #pragma unroll
         for (int i = 0; i < PER; ++i)
             store_gemm_in<DT>(M.O, k, mm, head * HD + lane + 64 * i, num[i] * inv);
+        AMUSD_TP(3, wg, 5);
     }
 }
 
@@ -938,6 +980,15 @@ static hipError_t configure_one() {
 #undef AMUSD_SET
     return hipSuccess;
 }
+
+#ifdef AMUSD_TRACE
+extern "C" int amusd_debug_read_trace(unsigned long long* out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_trace), sizeof(unsigned long long) * 8 * 256 * 8);
+}
+extern "C" int amusd_debug_read_trace_wave(unsigned long long* out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_trace_wave), sizeof(unsigned long long) * 8 * 256 * 8);
+}
+#endif
 
 hipError_t configure_kernels() {
     hipError_t e;
