@@ -18,6 +18,10 @@ import os
 import sys
 import time
 
+# Kernel arguments in device memory instead of host memory: the first scalar load of every kernel
+# then misses to HBM, not across PCIe.  Must be set before the HIP runtime initialises.
+os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
+
 import numpy as np
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -93,6 +97,8 @@ def main():
     ap.add_argument("--single-kernel", type=int, default=0)
     ap.add_argument("--time-stage", default="gateup", help="stage bracketed with HIP events ('none' to disable)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="run only a plain copy kernel of this size 10 times (profiler byte-counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
@@ -106,6 +112,17 @@ def main():
     import paper_2410_17375_amd as A
     from paper_2410_17375_amd.harness import load_model
     from workload import SHAPES, prompt_tokens, corrupt_drafts
+
+    if args.calibrate_copy:
+        n = args.calibrate_copy << 20
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        for _ in range(10):
+            A.calibration_copy(dst.data_ptr(), src.data_ptr(), n)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration_copy_bytes_read": n, "calibration_copy_bytes_written": n, "launches": 10}))
+        return
 
     shape_name, L0, k, seed = WORKLOADS[args.workload]
     shape = SHAPES[shape_name]

@@ -230,6 +230,12 @@ int amusd_get_kv(amusd_model *m, int32_t layer, int32_t which, int32_t pos0, int
 int64_t amusd_weight_bytes_per_pass(const amusd_model *m);
 int64_t amusd_kv_bytes_per_pass(const amusd_model *m, int32_t ctx_len, int32_t k);
 
+/* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16; both
+ * pointers device memory, 16-byte aligned) on the given HIP stream.  Not part
+ * of the method: a kernel of exactly known traffic (bytes read + bytes written)
+ * against which profiler byte counters are calibrated. */
+int amusd_calibration_copy(void *dst, const void *src, int64_t bytes, void *hip_stream);
+
 /* Static description of a code; amusd_last_error gives the calling thread's
  * most recent detailed message (e.g. the HIP error string). */
 const char *amusd_strerror(int code);

@@ -83,6 +83,7 @@ def _load():
         "amusd_get_kv": (C.c_int, [vp, i32, i32, i32, i32, f32p]),
         "amusd_weight_bytes_per_pass": (C.c_int64, [vp]),
         "amusd_kv_bytes_per_pass": (C.c_int64, [vp, i32, i32]),
+        "amusd_calibration_copy": (C.c_int, [vp, vp, C.c_int64, vp]),
         "amusd_strerror": (C.c_char_p, [C.c_int]),
         "amusd_last_error": (C.c_char_p, []),
     }
@@ -205,6 +206,10 @@ class Model:
 
     def kv_bytes_per_pass(self, ctx_len, k):
         return lib.amusd_kv_bytes_per_pass(self._h, ctx_len, k)
+
+
+def calibration_copy(dst_ptr, src_ptr, nbytes, stream=0):
+    _check(lib.amusd_calibration_copy(C.c_void_p(dst_ptr), C.c_void_p(src_ptr), nbytes, C.c_void_p(stream)))
 
 
 def _loop(fn, models, prompt, n_new, k_max):

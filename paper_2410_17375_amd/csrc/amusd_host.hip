@@ -140,6 +140,27 @@ float bf16_bits_to_float(uint16_t b) {
     return f;
 }
 
+float half_bits_to_float(uint16_t h) {      // IEEE binary16 -> float
+    const uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    uint32_t e = (h >> 10) & 0x1Fu, f = h & 0x3FFu, u;
+    if (e == 0) {
+        if (f == 0) {
+            u = sign;
+        } else {                             // subnormal: normalise
+            int sh = 0;
+            while (!(f & 0x400u)) { f <<= 1; ++sh; }
+            u = sign | ((uint32_t)(113 - sh) << 23) | ((f & 0x3FFu) << 13);
+        }
+    } else if (e == 31) {
+        u = sign | 0x7F800000u | (f << 13);
+    } else {
+        u = sign | ((e + 112) << 23) | (f << 13);
+    }
+    float r;
+    std::memcpy(&r, &u, 4);
+    return r;
+}
+
 std::once_flag g_cfg_once;
 hipError_t g_cfg_err = hipSuccess;
 
@@ -603,8 +624,8 @@ int amusd_get_kv(amusd_model* m, int32_t layer, int32_t which, int32_t pos0, int
     std::vector<char> raw(elems * esz);
     HIP_TRY(hipMemcpy(raw.data(), which ? m->layers_host[layer].vcache : m->layers_host[layer].kcache, raw.size(),
                       hipMemcpyDeviceToHost));
-    auto val = [&](size_t i) {
-        return esz == 2 ? bf16_bits_to_float(reinterpret_cast<const uint16_t*>(raw.data())[i])
+    auto val = [&](size_t i) {   // the cache of a 16-bit model holds IEEE half
+        return esz == 2 ? half_bits_to_float(reinterpret_cast<const uint16_t*>(raw.data())[i])
                         : reinterpret_cast<const float*>(raw.data())[i];
     };
     for (int h = 0; h < D.Hkv; ++h)
@@ -638,6 +659,13 @@ int64_t amusd_kv_bytes_per_pass(const amusd_model* m, int32_t ctx_len, int32_t k
     if (!m) return fail(AMUSD_E_ARG, "null model");
     const amusd_config& c = m->cfg;
     return (int64_t)c.n_layers * 2 * c.n_kv_heads * c.head_dim * m->esz() * ((int64_t)ctx_len + k);
+}
+
+int amusd_calibration_copy(void* dst, const void* src, int64_t bytes, void* hip_stream) {
+    if (!dst || !src || bytes < 16 || bytes % 16) return fail(AMUSD_E_ARG, "calibration_copy: bad argument");
+    HIP_TRY(launch_copy(reinterpret_cast<uint4*>(dst), reinterpret_cast<const uint4*>(src), (size_t)bytes / 16,
+                        reinterpret_cast<hipStream_t>(hip_stream)));
+    return AMUSD_OK;
 }
 
 // ---- drivers ------------------------------------------------------------------------------------

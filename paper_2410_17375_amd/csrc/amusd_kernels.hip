@@ -18,12 +18,15 @@
 //     activation side; weights are exact bf16.
 // Every stage is a __device__ function over (workgroup id, workgroup count) so
 // the same code runs as one kernel per stage or inside one persistent kernel.
+#include <hip/hip_fp16.h>
+
 #include "amusd_launch.h"
 
 namespace amusd {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 
 // ---------------------------------------------------------------- dtype traits
 struct BF16 {
@@ -36,6 +39,17 @@ struct BF16 {
     static __device__ __forceinline__ v4f mfma(uint4 a, uint4 b, v4f c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
     }
+    // Attention operands (cache, queries, probabilities) are IEEE half: the same 2 bytes per element as
+    // bf16 with three more mantissa bits; their magnitudes (keys, values, queries O(1), probabilities
+    // in [0,1]) sit well inside the half range, and stores clamp to it.
+    static __device__ __forceinline__ v4f mfma_att(uint4 a, uint4 b, v4f c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ uint32_t att_bits(float x) {
+        const float c = fminf(fmaxf(x, -65504.f), 65504.f);
+        return (uint32_t)__half_as_ushort(__float2half_rn(c));
+    }
+    static __device__ __forceinline__ float att_float(uint32_t b) { return __half2float(__ushort_as_half((unsigned short)b)); }
 };
 struct FP32 {
     static constexpr int EPL = 4;
@@ -51,6 +65,9 @@ struct FP32 {
         c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
         return c;
     }
+    static __device__ __forceinline__ v4f mfma_att(uint4 a, uint4 b, v4f c) { return mfma(a, b, c); }
+    static __device__ __forceinline__ uint32_t att_bits(float x) { return __float_as_uint(x); }
+    static __device__ __forceinline__ float att_float(uint32_t b) { return __uint_as_float(b); }
 };
 
 #ifdef AMUSD_TRACE
@@ -72,12 +89,12 @@ __device__ __forceinline__ uint32_t bf16_rne(float x) {
 }
 __device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
-// store x into an activation buffer: fp32 as is; bf16 as hi + lo
+// store a query element: fp32 as is; 16-bit models as hi + lo halves of the attention element type
 template <class DT>
 __device__ __forceinline__ void store_act(void* hi, void* lo, size_t idx, float x) {
     if constexpr (DT::HAS_LO) {
-        uint32_t h = bf16_rne(x);
-        uint32_t l = bf16_rne(x - bf16_to_f32(h));
+        uint32_t h = DT::att_bits(x);
+        uint32_t l = DT::att_bits(x - DT::att_float(h));
         reinterpret_cast<uint16_t*>(hi)[idx] = (uint16_t)h;
         reinterpret_cast<uint16_t*>(lo)[idx] = (uint16_t)l;
     } else {
@@ -450,8 +467,8 @@ struct EpiQKV {
             } else {
                 const size_t o = ((size_t)head * M.ctx_pad + pos) * hd + i;
                 if constexpr (DT::HAS_LO) {
-                    reinterpret_cast<uint16_t*>(Ly.kcache)[o] = (uint16_t)bf16_rne(y1);
-                    reinterpret_cast<uint16_t*>(Ly.kcache)[o + hd / 2] = (uint16_t)bf16_rne(y2);
+                    reinterpret_cast<uint16_t*>(Ly.kcache)[o] = (uint16_t)DT::att_bits(y1);
+                    reinterpret_cast<uint16_t*>(Ly.kcache)[o + hd / 2] = (uint16_t)DT::att_bits(y2);
                 } else {
                     reinterpret_cast<float*>(Ly.kcache)[o] = y1;
                     reinterpret_cast<float*>(Ly.kcache)[o + hd / 2] = y2;
@@ -467,8 +484,8 @@ struct EpiQKV {
             const size_t o1 = (blk * 64 + gg * 16 + r) * DT::EPL + e;
             const size_t o2 = (blk * 64 + gg * 16 + r + 8) * DT::EPL + e;
             if constexpr (DT::HAS_LO) {
-                reinterpret_cast<uint16_t*>(Ly.vcache)[o1] = (uint16_t)bf16_rne(x1);
-                reinterpret_cast<uint16_t*>(Ly.vcache)[o2] = (uint16_t)bf16_rne(x2);
+                reinterpret_cast<uint16_t*>(Ly.vcache)[o1] = (uint16_t)DT::att_bits(x1);
+                reinterpret_cast<uint16_t*>(Ly.vcache)[o2] = (uint16_t)DT::att_bits(x2);
             } else {
                 reinterpret_cast<float*>(Ly.vcache)[o1] = x1;
                 reinterpret_cast<float*>(Ly.vcache)[o2] = x2;
@@ -704,8 +721,8 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
                 v4f sc = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int i = 0; i < FR; ++i) {
-                    sc = DT::mfma(kf[t][i], qh[i], sc);
-                    if constexpr (DT::HAS_LO) sc = DT::mfma(kf[t][i], ql[i], sc);
+                    sc = DT::mfma_att(kf[t][i], qh[i], sc);
+                    if constexpr (DT::HAS_LO) sc = DT::mfma_att(kf[t][i], ql[i], sc);
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -738,8 +755,8 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
                 for (int t = 0; t < TPB; ++t)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        h[t * 4 + e] = bf16_rne(pv[t][e]);
-                        l[t * 4 + e] = bf16_rne(pv[t][e] - bf16_to_f32(h[t * 4 + e]));
+                        h[t * 4 + e] = DT::att_bits(pv[t][e]);
+                        l[t * 4 + e] = DT::att_bits(pv[t][e] - DT::att_float(h[t * 4 + e]));
                     }
                 ph = uint4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
                 pl = uint4{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
@@ -749,8 +766,8 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
 #pragma unroll
             for (int j = 0; j < HT; ++j) {
                 o[j] = o[j] * alpha;
-                o[j] = DT::mfma(vf[j], ph, o[j]);
-                if constexpr (DT::HAS_LO) o[j] = DT::mfma(vf[j], pl, o[j]);
+                o[j] = DT::mfma_att(vf[j], ph, o[j]);
+                if constexpr (DT::HAS_LO) o[j] = DT::mfma_att(vf[j], pl, o[j]);
             }
 #pragma unroll
             for (int t = 0; t < TPB; ++t)
@@ -819,6 +836,15 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassAr
         float Mrun = -INFINITY, den = 0.f, num[PER];
 #pragma unroll
         for (int i = 0; i < PER; ++i) num[i] = 0.f;
+        // numerators of the first chunks are fetched together with the maxima: one memory round trip
+        constexpr int CPRE = 24;
+        float pre[CPRE][PER];
+#pragma unroll
+        for (int j = 0; j < CPRE; ++j) {
+            const float* pj = base + (size_t)(j < nch ? j : nch - 1) * cstride;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) pre[j][i] = pj[lane + 64 * i];
+        }
         for (int c0 = 0; c0 < nch; c0 += 64) {        // groups of 64 chunks, in order
             const int cc = c0 + lane;
             const bool on = cc < nch;
@@ -838,7 +864,15 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassAr
 #pragma unroll
             for (int i = 0; i < PER; ++i) num[i] *= scale_old;
             const int ng = nch - c0 < 64 ? nch - c0 : 64;
-            for (int j = 0; j < ng; ++j) {
+            if (c0 == 0) {
+#pragma unroll
+                for (int j = 0; j < CPRE; ++j) {
+                    const float wj = j < ng ? __shfl(wt, j, 64) : 0.f;
+#pragma unroll
+                    for (int i = 0; i < PER; ++i) num[i] += wj * pre[j][i];
+                }
+            }
+            for (int j = c0 == 0 ? CPRE : 0; j < ng; ++j) {
                 const float wj = __shfl(wt, j, 64);
                 const float* pj = base + (size_t)(c0 + j) * cstride;
 #pragma unroll
@@ -958,6 +992,16 @@ hipError_t launch_relayout(int dtype, uint4* dst, const void* src, int K, int n_
         hipLaunchKernelGGL(k_relayout<BF16>, dim3(grid), dim3(256), 0, stream, dst, src, K, n_tiles, tile_offset, kind, hd);
     else
         hipLaunchKernelGGL(k_relayout<FP32>, dim3(grid), dim3(256), 0, stream, dst, src, K, n_tiles, tile_offset, kind, hd);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- plain copy (profiler calibration)
+__global__ void __launch_bounds__(256) k_plain_copy(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
+hipError_t launch_copy(uint4* dst, const uint4* src, size_t n, hipStream_t stream) {
+    hipLaunchKernelGGL(k_plain_copy, dim3(2048), dim3(256), 0, stream, dst, src, n);
     return hipGetLastError();
 }
 

@@ -27,6 +27,9 @@ struct StageTimer {
     int used = 0;                  // pairs recorded by the last launch_pass
 };
 
+// Plain copy of n 16-byte words (profiler calibration).
+hipError_t launch_copy(uint4* dst, const uint4* src, size_t n, hipStream_t stream);
+
 // Enqueues one whole pass (all stages) on the stream.
 hipError_t launch_pass(const DevModel& M, const DevLayer* layers_host, const PassArgs& P, int nwg, hipStream_t stream,
                        bool single_kernel, StageTimer* timer);

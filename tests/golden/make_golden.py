@@ -36,6 +36,10 @@ WORKLOADS = {
     "8b_k16_ctx16384": ("8b", 16384, 16, 3, (0.3,)),
     "1b_k5_ctx512": ("1b", 512, 5, 1, (0.3,)),
 }
+# greedy-sequence workloads: name -> (shape, prompt length, tokens to generate, seed)
+GREEDY = {
+    "8b_greedy_p128_n256": ("8b", 128, 256, 4),
+}
 N_SAMPLED_IDS = 64
 
 
@@ -58,12 +62,42 @@ def describe_rows(logits, ids):
     return rows
 
 
+def greedy_sequence(name, out_path):
+    """The verify model's plain greedy continuation of a prompt with the top-2
+    margin at every position (the reference of the full decoding loops)."""
+    shape_name, P, N, seed = GREEDY[name]
+    shape = SHAPES[shape_name]
+    store = WeightStore(shape, cache=False)
+    dec = Decoder(shape, store, P + N + 1, dtype=np.float32, keep_weights=True)   # fp32 weights stay in memory
+    dec.progress = log
+    prompt = prompt_tokens(seed, P, shape.vocab)
+    z = dec.rows(prompt, logits_from=P - 1)
+    dec.progress = None
+    toks, margins = [argmax_lowest(z[-1])], [top2_margin(z[-1])]
+    for i in range(1, N):
+        z = dec.step(toks[-1])
+        toks.append(argmax_lowest(z))
+        margins.append(top2_margin(z))
+        if i % 16 == 0:
+            log(f"  {i}/{N} tokens")
+    doc = {"workload": name, "shape": shape_name, "prompt_len": P, "n_new": N, "seed": seed,
+           "oracle_dtype": "float32", "prompt_sha256": hashlib.sha256(prompt.tobytes()).hexdigest(),
+           "tokens": [int(t) for t in toks], "margins": margins}
+    with open(out_path, "w") as f:
+        json.dump(doc, f, indent=1)
+    log(f"wrote {out_path}")
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("workload", choices=sorted(WORKLOADS))
+    ap.add_argument("workload", choices=sorted(WORKLOADS) + sorted(GREEDY))
     ap.add_argument("--out")
     ap.add_argument("--block", type=int, default=512, help="context rows per batched oracle pass")
     args = ap.parse_args()
+    if args.workload in GREEDY:
+        greedy_sequence(args.workload, args.out or os.path.join(os.path.dirname(os.path.abspath(__file__)),
+                                                                args.workload + ".json"))
+        return
     shape_name, L0, k, seed, ps = WORKLOADS[args.workload]
     shape = SHAPES[shape_name]
     out_path = args.out or os.path.join(os.path.dirname(os.path.abspath(__file__)), args.workload + ".json")
