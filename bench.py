@@ -37,6 +37,9 @@ WORKLOADS = {
     "tiny_fp32_k4_ctx64": ("tiny_verify", 64, 4, 0),
 }
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes per launch of the timed stage (fetched + written), from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# recorded in profiles/ (counter readings scaled by the plain-copy calibration: 2.000 and 1.000 KiB per count).
+MEASURED_TRAFFIC = {("8b_bf16_k8_ctx2048", "gateup"): 236_668_000}
 
 
 def log(msg):
@@ -187,7 +190,7 @@ def main():
         ach = b / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
         out["roofline"] = {"bound": "hbm", "kernel": args.time_stage, "achieved": round(ach, 1),
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
-                           "traffic": None, "avg_launch_ms": round(avg_ms, 5), "launches": int(launches),
+                           "traffic": MEASURED_TRAFFIC.get((args.workload, args.time_stage)), "avg_launch_ms": round(avg_ms, 5), "launches": int(launches),
                            "algorithmic_bytes_per_launch": int(b)}
     if not args.no_cpu_baseline:
         try:

@@ -135,7 +135,7 @@ int amusd_model_free(amusd_model *m);
 /* ---- the steps of Algorithm 1 ------------------------------------------------------------- */
 
 /* "Initialize key-value caches with x": appends n tokens (host array) at
- * positions kv_len .. kv_len+n-1 unconditionally, max_k rows per pass, and
+ * positions kv_len .. kv_len+n-1 unconditionally, several rows per pass, and
  * returns in *next_token the greedy token after the last one.  next_token may
  * be NULL.  Errors: ARG, TOKEN, CAPACITY. */
 int amusd_prefill(amusd_model *m, const int32_t *tokens, int32_t n, int32_t *next_token);

@@ -18,6 +18,7 @@
 //     activation side; weights are exact bf16.
 // Every stage is a __device__ function over (workgroup id, workgroup count) so
 // the same code runs as one kernel per stage or inside one persistent kernel.
+#include <hip/hip_ext.h>
 #include <hip/hip_fp16.h>
 
 #include "amusd_launch.h"
@@ -1056,34 +1057,37 @@ static hipError_t launch_pass_t(const DevModel& M, const DevLayer* Ls, const Pas
     const int d_wgs = M.d / 16 < nwg ? M.d / 16 : nwg;
     const int gu_wgs = 2 * M.F / 16 < nwg ? 2 * M.F / 16 : nwg;
     if (tm) tm->used = 0;
-    auto mark = [&](int stage, bool begin) {
-        if (tm && tm->stage == stage) {
-            (void)hipEventRecord(begin ? tm->begin[tm->used] : tm->end[tm->used], s);
-            if (!begin) ++tm->used;
-        }
-    };
+    // A timed stage is launched through the extended launch call, whose two events take the kernel's own
+    // begin and end timestamps (no marker packets around it).
     const float* nogain = nullptr;
-#define AMUSD_LAUNCH(stage, kern, grid, smem, layer, gain)                                  \
-    mark(stage, true);                                                                       \
-    hipLaunchKernelGGL((kern<DT, HD>), dim3(grid), blk, smem, s, M, Ls[layer], gain, P);    \
-    mark(stage, false);
+#define AMUSD_LAUNCH_T(stage_id, kern, grid, block, smem, layer, gain)                                          \
+    if (tm && tm->stage == stage_id) {                                                                            \
+        hipExtLaunchKernelGGL((kern<DT, HD>), dim3(grid), block, smem, s, tm->begin[tm->used], tm->end[tm->used], \
+                              0, M, Ls[layer], gain, P);                                                        \
+        ++tm->used;                                                                                              \
+    } else {                                                                                                     \
+        hipLaunchKernelGGL((kern<DT, HD>), dim3(grid), block, smem, s, M, Ls[layer], gain, P);                  \
+    }
+#define AMUSD_LAUNCH(stage_id, kern, grid, smem, layer, gain) AMUSD_LAUNCH_T(stage_id, kern, grid, blk, smem, layer, gain)
     AMUSD_LAUNCH(0, k_embed, embed_wgs, 0, 0, Ls[0].g_attn)
     for (int l = 0; l < M.n_layers; ++l) {
         const float* gain_next = l + 1 < M.n_layers ? Ls[l + 1].g_attn : M.g_final;
         AMUSD_LAUNCH(1, k_qkv, qkv_wgs, kSmemBytes, l, nogain)
         AMUSD_LAUNCH(2, k_attention, att_wgs, kSmemBytes, l, nogain)
-        mark(3, true);
-        hipLaunchKernelGGL((k_attn_merge<DT, HD>), dim3(merge_wgs), dim3(64), 0, s, M, Ls[l], nogain, P);
-        mark(3, false);
+        AMUSD_LAUNCH_T(3, k_attn_merge, merge_wgs, dim3(64), 0, l, nogain)
         AMUSD_LAUNCH(4, k_oproj, d_wgs, kSmemBytes, l, nogain)
         AMUSD_LAUNCH(5, k_gateup, gu_wgs, kSmemBytes, l, nogain)
         AMUSD_LAUNCH(6, k_down, d_wgs, kSmemBytes, l, gain_next)
     }
     AMUSD_LAUNCH(7, k_lmhead, M.lm_wgs, kSmemBytes, 0, nogain)
 #undef AMUSD_LAUNCH
-    mark(8, true);
-    hipLaunchKernelGGL(k_accept, dim3(1), dim3(kRows * 64), 0, s, M, P);
-    mark(8, false);
+#undef AMUSD_LAUNCH_T
+    if (tm && tm->stage == 8) {
+        hipExtLaunchKernelGGL(k_accept, dim3(1), dim3(kRows * 64), 0, s, tm->begin[0], tm->end[0], 0, M, P);
+        tm->used = 1;
+    } else {
+        hipLaunchKernelGGL(k_accept, dim3(1), dim3(kRows * 64), 0, s, M, P);
+    }
     return hipGetLastError();
 }
 

@@ -194,8 +194,8 @@ def test_full_asynchronous_loop_reproduces_greedy_sequence():
         v.kv_rollback(0)
         g0 = v.prefill(prompt)
         got = [g0]
-        for s in range(0, len(toks) - 1, 16):
-            chunk = toks[s:s + 16][:len(toks) - 1 - s]
+        for s in range(0, len(toks) - 1, 8):
+            chunk = toks[s:s + 8][:len(toks) - 1 - s]
             v.prefill(chunk)
             got += list(v.get_greedy(len(chunk)))
         checked = 0

@@ -68,11 +68,13 @@ def test_prefill_and_verify_rounds_match_oracle(name):
         ref = o.dec.rows(piece)
         for j in range(n):
             o.greedy_at[pos + j + 1] = int(np.argmax(ref[j]))
-        err, flagged = _check_rows(shape, g, ref, n, f"{name} prefill@{pos}")
+        # 16-bit models prefill at most 8 rows per pass; the logits kept are those of the last pass
+        last = n if shape.dtype == "fp32" else (n - 1) % 8 + 1
+        err, flagged = _check_rows(shape, g, ref[n - last:], last, f"{name} prefill@{pos}")
         worst = max(worst, err)
         pos += n
         assert g.kv_len() == pos
-        if n - 1 not in flagged:
+        if last - 1 not in flagged:
             assert nxt == int(np.argmax(ref[-1]))
     assert pos == 64
     o.p_next = int(o.greedy_at[64])
@@ -119,8 +121,9 @@ def test_k_row_pass_equals_k_single_row_passes_bitwise(name):
     a.prefill(toks[:270])
     b.prefill(toks[:270])
     for L, k in ((270, 16), (286, 5), (291, 9)):
-        a.prefill(toks[L:L + k])
+        a.verify(L, toks[L:L + k])            # one k-row pass (whatever it accepts, all k rows are computed)
         za = a.get_logits(k)
+        a.prefill(toks[a.kv_len():L + k])     # bring the cache to L + k
         for j in range(k):
             b.prefill(toks[L + j:L + j + 1])
             zb = b.get_logits(1)
