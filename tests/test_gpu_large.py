@@ -207,3 +207,75 @@ def test_full_asynchronous_loop_reproduces_greedy_sequence():
         assert checked >= len(toks) // 2
     for mm in (v, d, twin):
         mm.free()
+
+
+def test_long_context_stress_16k_rollback_and_reextend():
+    """8B shape, context 16384, k = 16, p = 0.3: every round rolls back to a uniformly random point of
+    the accepted prefix and re-extends.  Attention-bound verify, repeated truncate / re-extend."""
+    A, load_model, _ = _gpu()
+    from workload import rollback_points
+    shape, L0, k = SHAPES["8b"], 16384, 16
+    say("16K: loading the 8B-shape model")
+    m = load_model(shape, L0 + 256)
+    m.set_option(A.OPT_KEEP_LOGITS, 1)
+    prompt = prompt_tokens(3, L0, shape.vocab)
+    say("16K: prefilling 16384 tokens on the GPU")
+    first = m.prefill(prompt)
+    path = os.path.join(GOLDEN, "8b_k16_ctx16384.json")
+    if os.path.exists(path):
+        gold = json.load(open(path))
+        assert hashlib.sha256(prompt.tobytes()).hexdigest() == gold["prompt_sha256"]
+        c = gold["continuation"]
+        ids = np.array(gold["sampled_ids"])
+        worst = 0.0
+        for w in gold["windows"]:
+            m.kv_rollback(L0)
+            m.set_next(c[0])
+            n, nxt = m.verify(L0, np.array(w["draft"], dtype=np.int32))
+            z, gg = m.get_logits(k), m.get_greedy(k)
+            flagged = []
+            for j, row in enumerate(w["rows"]):
+                e = max(np.abs(z[j, row["top_ids"]] - np.array(row["top_logits"])).max(),
+                        np.abs(z[j, ids] - np.array(row["sampled_logits"])).max())
+                worst = max(worst, e)
+                assert e <= TOL, f"16K window {w['name']} row {j}: logit error {e:.3e}"
+                if row["margin"] < TOL:
+                    flagged.append(j)
+                else:
+                    assert gg[j] == row["argmax"]
+            if not any(j <= min(w["accept_len"], k - 1) for j in flagged):
+                assert (n, nxt) == (w["accept_len"], w["next_token"]), w["name"]
+        say(f"16K: stored oracle values matched, worst sampled logit error {worst:.3e}")
+    else:
+        say("16K: stored oracle values missing, property checks only")
+    # the model's own greedy continuation, then the stress rounds
+    m.kv_rollback(L0)
+    cont = [first]
+    for _ in range(k + 40):
+        cont.append(m.draft_step())
+    full = np.concatenate([prompt, np.array(cont, dtype=np.int32)])
+    L, hist = L0, np.zeros(k + 1, dtype=int)
+    for r in range(24):
+        m.kv_rollback(L)
+        draft = corrupt_drafts(3, r, full[L:L + k], 0.3, shape.vocab)
+        n, nxt = m.verify(L, draft)
+        hist[n] += 1
+        # accepted rows are the greedy path; the token after them is the model's own
+        assert np.array_equal(draft[:n], full[L:L + n]) and nxt == full[L + n]
+        assert m.kv_len() == L + n
+        z1 = m.get_logits(k).copy()
+        if r % 8 == 0:                         # the same pass again after an O(1) truncation: same bits
+            m.kv_rollback(L)
+            n2, nxt2 = m.verify(L, draft)
+            assert (n2, nxt2) == (n, nxt) and np.array_equal(m.get_logits(k), z1)
+        if r % 12 == 0:                        # ... and as 16 one-row passes
+            m.kv_rollback(L)
+            for j in range(k):
+                m.prefill(draft[j:j + 1])
+                assert np.array_equal(m.get_logits(1)[0], z1[j]), (r, j)
+            m.kv_rollback(L + n)
+        L = L + rollback_points(3, r, n)
+        if L + k + 1 >= len(full):
+            break
+    say(f"16K: accept-length histogram over the stress rounds {hist.tolist()}, final context {L}")
+    m.free()
