@@ -36,7 +36,7 @@ struct DevLayer {
     const uint4* wd;     // [d/16][F/KB][64]
     const float* g_attn; // [d]
     const float* g_mlp;  // [d]
-    void* kcache;        // [Hkv][ctx_pad][hd] elements
+    void* kcache;        // [Hkv][ctx_pad/16][hd/4/EPL][64 lanes][EPL] elements (operand order of the score product)
     void* vcache;        // [Hkv][ctx_pad/BK][hd/16][64 lanes][EPL] elements (matrix-core operand order)
 };
 

@@ -636,7 +636,9 @@ int amusd_get_kv(amusd_model* m, int32_t layer, int32_t which, int32_t pos0, int
                 const int pos = pos0 + j;
                 size_t idx;
                 if (!which) {
-                    idx = ((size_t)h * D.ctx_pad + pos) * hd + c;
+                    const int q4 = hd / 4, g = c / q4, w = c % q4;
+                    idx = (size_t)h * D.ctx_pad * hd +
+                          ((((size_t)(pos >> 4) * (q4 / EPL) + w / EPL) * 64) + g * 16 + (pos & 15)) * EPL + w % EPL;
                 } else {
                     const int b = pos / BK, q = pos % BK;
                     const int e = (q / 16) * 4 + (q % 4), gg = (q % 16) / 4;

@@ -135,6 +135,16 @@ __device__ __forceinline__ void store_gemm_in(void* buf, int k_rows, int m, int 
     }
 }
 
+// Element index of key `pos`, head_dim column `c` in a kv head's key cache.  Keys are kept in the operand
+// order of the score product: [16-key tile][fragment i][lane = g*16 + key%16][EPL], where lane group g owns
+// columns g*hd/4 .. (g+1)*hd/4 and fragment i its i-th run of EPL columns, so a wave fetches one
+// (tile, fragment) with a single contiguous 1 KiB load.
+template <class DT>
+__device__ __forceinline__ size_t kcache_index(int hd, int pos, int c) {
+    const int q = hd / 4, g = c / q, w = c % q;
+    return ((((size_t)(pos >> 4) * (q / DT::EPL) + w / DT::EPL) * 64) + g * 16 + (pos & 15)) * DT::EPL + w % DT::EPL;
+}
+
 // Weights are read once per pass: a non-temporal load keeps them from evicting
 // the (re-read) activations from L2.
 __device__ __forceinline__ uint4 load_stream(const uint4* p) {
@@ -466,13 +476,14 @@ struct EpiQKV {
                 store_act<DT>(M.Q_hi, M.Q_lo, o, y1);
                 store_act<DT>(M.Q_hi, M.Q_lo, o + hd / 2, y2);
             } else {
-                const size_t o = ((size_t)head * M.ctx_pad + pos) * hd + i;
+                const size_t hb = (size_t)head * M.ctx_pad * hd;
+                const size_t o1 = hb + kcache_index<DT>(hd, pos, i), o2 = hb + kcache_index<DT>(hd, pos, i + hd / 2);
                 if constexpr (DT::HAS_LO) {
-                    reinterpret_cast<uint16_t*>(Ly.kcache)[o] = (uint16_t)DT::att_bits(y1);
-                    reinterpret_cast<uint16_t*>(Ly.kcache)[o + hd / 2] = (uint16_t)DT::att_bits(y2);
+                    reinterpret_cast<uint16_t*>(Ly.kcache)[o1] = (uint16_t)DT::att_bits(y1);
+                    reinterpret_cast<uint16_t*>(Ly.kcache)[o2] = (uint16_t)DT::att_bits(y2);
                 } else {
-                    reinterpret_cast<float*>(Ly.kcache)[o] = y1;
-                    reinterpret_cast<float*>(Ly.kcache)[o + hd / 2] = y2;
+                    reinterpret_cast<float*>(Ly.kcache)[o1] = y1;
+                    reinterpret_cast<float*>(Ly.kcache)[o2] = y2;
                 }
             }
         } else {
@@ -694,12 +705,12 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
         uint4 kf[TPB][FR], vf[HT];
         auto load_block = [&](int b, uint4 (&kd)[TPB][FR], uint4 (&vd)[HT]) {
             const int bb = b < nblk ? b : nblk - 1;    // stay inside the cache allocation
+            const uint4* kb = reinterpret_cast<const uint4*>(Ly.kcache) +
+                              ((size_t)kvh * (M.ctx_pad / 16) + (size_t)bb * TPB) * FR * 64 + lane;
 #pragma unroll
-            for (int t = 0; t < TPB; ++t) {
-                const size_t e0 = ((size_t)kvh * M.ctx_pad + bb * BK + t * 16 + m) * HD + g * (HD / 4);
+            for (int t = 0; t < TPB; ++t)
 #pragma unroll
-                for (int i = 0; i < FR; ++i) kd[t][i] = load_frag<DT>(Ly.kcache, e0 + i * DT::EPL);
-            }
+                for (int i = 0; i < FR; ++i) kd[t][i] = kb[(t * FR + i) * 64];
             const uint4* vb = reinterpret_cast<const uint4*>(Ly.vcache) + (((size_t)kvh * nblk + bb) * HT) * 64 + lane;
 #pragma unroll
             for (int j = 0; j < HT; ++j) vd[j] = vb[j * 64];
