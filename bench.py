@@ -100,6 +100,11 @@ def main():
     ap.add_argument("--single-kernel", type=int, default=0)
     ap.add_argument("--time-stage", default="gateup", help="stage bracketed with HIP events ('none' to disable)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--loops", action="store_true",
+                    help="instead of the verify-pass benchmark, time the three decoding strategies of the paper's "
+                         "Table 1 (autoregressive, synchronous speculative, asynchronous) on one GPU: 8B-shape verify "
+                         "model, 128-token prompt, 256 new tokens, with a random-weight 1B-shape draft model (nothing "
+                         "it proposes is accepted) and with a copy of the verify model as draft (everything is)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="run only a plain copy kernel of this size 10 times (profiler byte-counter calibration)")
     args = ap.parse_args()
@@ -125,6 +130,27 @@ def main():
             A.calibration_copy(dst.data_ptr(), src.data_ptr(), n)
         torch.cuda.synchronize()
         print(json.dumps({"calibration_copy_bytes_read": n, "calibration_copy_bytes_written": n, "launches": 10}))
+        return
+
+    if args.loops:
+        sv, sd = SHAPES["8b"], SHAPES["1b_v128k"]
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        log("loading verify (8B shape), draft (1B shape) and twin models ...")
+        v = load_model(sv, 512, stream=s1.cuda_stream)
+        d = load_model(sd, 512, stream=s2.cuda_stream)
+        twin = load_model(sv, 512, stream=s2.cuda_stream)
+        prompt = prompt_tokens(4, 128, sv.vocab)
+        res = {}
+        ref, st = A.generate_greedy(v, prompt, 256)
+        res["autoregressive"] = {"ms_per_token": st["wall_ms"] / 256}
+        for name, dm in (("random_1b_draft", d), ("twin_draft", twin)):
+            for kind, fn in (("sync", A.generate_sync), ("async", A.generate_async)):
+                out, st = fn(dm, v, prompt, 256, 8)
+                assert np.array_equal(out, ref), f"{kind}/{name}: output differs from the greedy sequence"
+                res[f"{kind}_{name}"] = {"ms_per_token": st["wall_ms"] / 256, "rounds": st["rounds"],
+                                         "rollbacks": st["rollbacks"], "draft_steps": st["draft_steps"],
+                                         "accepted_per_round": st["accepted_total"] / max(st["rounds"], 1)}
+        print(json.dumps({"loops": res, "n_new": 256, "prompt": 128, "k_max": 8, "identical_output": True}))
         return
 
     shape_name, L0, k, seed = WORKLOADS[args.workload]
