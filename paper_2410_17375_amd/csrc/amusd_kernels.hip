@@ -112,8 +112,8 @@ __device__ __forceinline__ void store_act(void* hi, void* lo, size_t idx, float 
 //                 8-15 their lo halves (x = hi + lo), so one MFMA yields W.hi in
 //                 result columns 0-7 and W.lo in columns 8-15;
 //   bf16, k > 8 : two parts (hi, lo), slot = row.
-// The two sums (W.hi and W.lo) are reduced separately and added at the end in
-// both bf16 forms, so a row's value does not depend on which form carried it.
+// In both bf16 forms a wave adds its W.hi and W.lo sums before the cross-wave
+// reduction, so a row's value does not depend on which form carried it.
 template <class DT>
 __device__ __forceinline__ void store_gemm_in(void* buf, int k_rows, int m, int col, float x) {
     const int kb = col / DT::KB, g = (col % DT::KB) / DT::EPL, e = col % DT::EPL;
@@ -214,10 +214,13 @@ enum { kActSingle = 0, kActPacked8 = 1, kActHiLo = 2 };
 constexpr int kOldShare = AMUSD_OLD_SHARE;   // sixteenths of a SIMD's K range given to its first wave
 
 template <class DT, int MODE, int NT, int D>
-__device__ __forceinline__ void gemm_accumulate(v4f (&acc)[kMaxTilesPerRound], const uint4* __restrict__ W, int tile0,
+__device__ __forceinline__ void gemm_accumulate(v4f (&out)[kMaxTilesPerRound], const uint4* __restrict__ W, int tile0,
                                                 int tile_stride, int kblocks, int kb0, int S,
                                                 const uint4* __restrict__ act, int lane) {
     constexpr int AF = MODE == kActHiLo ? 2 : 1;          // activation fragments per K block
+    v4f acc[NT * AF];
+#pragma unroll
+    for (int j = 0; j < NT * AF; ++j) acc[j] = v4f{0.f, 0.f, 0.f, 0.f};
     const uint4* wp[NT];
 #pragma unroll
     for (int j = 0; j < NT; ++j) wp[j] = W + ((size_t)(tile0 + tile_stride * j) * kblocks + kb0) * 64 + lane;
@@ -256,16 +259,30 @@ __device__ __forceinline__ void gemm_accumulate(v4f (&acc)[kMaxTilesPerRound], c
 #pragma unroll
             for (int f = 0; f < AF; ++f) acc[j * AF + f] = DT::mfma(wb[i][j], on ? ab[i][f] : z, acc[j * AF + f]);
     }
+    // The wave's W.hi and W.lo sums are added here, in one fixed order for every k: two accumulators of a
+    // tile (kActHiLo), or result columns m and m+8 of one accumulator (kActPacked8; lanes m < 8 keep the sum).
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        if constexpr (MODE == kActHiLo) {
+            out[j] = acc[2 * j] + acc[2 * j + 1];
+        } else if constexpr (MODE == kActPacked8) {
+            v4f lo;
+            lo.x = __shfl_xor(acc[j].x, 8, 64);
+            lo.y = __shfl_xor(acc[j].y, 8, 64);
+            lo.z = __shfl_xor(acc[j].z, 8, 64);
+            lo.w = __shfl_xor(acc[j].w, 8, 64);
+            out[j] = acc[j] + lo;
+        } else {
+            out[j] = acc[j];
+        }
+    }
 }
 
-// MODE as above; in kActHiLo every tile has two accumulators, so a round holds
-// at most 4 tiles.
+// MODE as above.  A wave hands one partial tile per output tile to the reduction, whatever the mode.
 template <class DT, int MODE, class Epi>
 __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_tiles, int kblocks,
                                              const void* __restrict__ A, int wg, int nwg, Epi& epi, float* smem) {
-    constexpr int SLOTS = kMaxTilesPerRound;                  // accumulator tiles per wave per round
-    constexpr int AF = MODE == kActHiLo ? 2 : 1;
-    constexpr int NTMAX = SLOTS / AF;
+    constexpr int SLOTS = kMaxTilesPerRound;                  // partial tiles per wave per round
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
     // K split: SIMD s hosts waves s and s+4; they share the K quarter of their SIMD.  The first wave of a
@@ -281,8 +298,7 @@ __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_
     AMUSD_TP(Epi::kStage, wg, 0);
     for (int i0 = 0; i0 < mine;) {
         const int left = mine - i0;
-        int nt = left >= 8 ? 8 : left == 7 ? 7 : left >= 4 ? 4 : left >= 2 ? 2 : 1;
-        if (nt > NTMAX) nt = NTMAX;
+        const int nt = left >= 8 ? 8 : left == 7 ? 7 : left >= 4 ? 4 : left >= 2 ? 2 : 1;
         const int t0 = wg + nwg * i0;
         epi.prefetch(t0, nwg, nt);
         if (first) AMUSD_TP(Epi::kStage, wg, 1);
@@ -292,6 +308,8 @@ __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_
         if (S > 0) {
             if constexpr (MODE == kActHiLo) {
                 switch (nt) {
+                    case 8: gemm_accumulate<DT, MODE, 8, 2>(acc, W, t0, nwg, kblocks, kb0, S, act, lane); break;
+                    case 7: gemm_accumulate<DT, MODE, 7, 2>(acc, W, t0, nwg, kblocks, kb0, S, act, lane); break;
                     case 4: gemm_accumulate<DT, MODE, 4, 3>(acc, W, t0, nwg, kblocks, kb0, S, act, lane); break;
                     case 2: gemm_accumulate<DT, MODE, 2, 6>(acc, W, t0, nwg, kblocks, kb0, S, act, lane); break;
                     default: gemm_accumulate<DT, MODE, 1, 8>(acc, W, t0, nwg, kblocks, kb0, S, act, lane); break;
@@ -307,9 +325,11 @@ __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_
             }
         }
         // partial tiles to LDS as [wave][slot][column m][n]; lane holds n = 4g..4g+3 of result column m
+        // (kActPacked8: columns 8..15 carry nothing the reduction reads)
 #pragma unroll
         for (int j = 0; j < SLOTS; ++j)
-            if (j < nt * AF) *reinterpret_cast<v4f*>(smem + ((wave * SLOTS + j) * 256 + m * 16 + g * 4)) = acc[j];
+            if (j < nt && (MODE != kActPacked8 || m < 8))
+                *reinterpret_cast<v4f*>(smem + ((wave * SLOTS + j) * 256 + m * 16 + g * 4)) = acc[j];
         if (first) AMUSD_TP(Epi::kStage, wg, 2);
 #ifdef AMUSD_TRACE
         if (first && lane == 0 && wg < 256) g_trace_wave[(Epi::kStage * 256 + wg) * 8 + wave] = wall_clock64();
@@ -318,29 +338,16 @@ __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_
         __syncthreads();
         if (first) AMUSD_TP(Epi::kStage, wg, 3);
 #pragma unroll
-        for (int it = 0; it * kThreads < NTMAX * 128; ++it) {
+        for (int it = 0; it * kThreads < SLOTS * 128; ++it) {
             const int item = tid + it * kThreads;
             const int j = item >> 7, mm = (item >> 3) & 15, r = item & 7;
             const bool valid = j < nt && (MODE != kActPacked8 || mm < 8);
             float v1 = 0.f, v2 = 0.f;
             if (valid) {
-                // slot and result column of the W.hi sum, and of the W.lo sum where there is one
-                const int sh = MODE == kActHiLo ? 2 * j : j, ch = mm;
-                const int sl = MODE == kActHiLo ? 2 * j + 1 : j, cl = MODE == kActPacked8 ? mm + 8 : mm;
 #pragma unroll
                 for (int w = 0; w < kWaves; ++w) {
-                    v1 += smem[(w * SLOTS + sh) * 256 + ch * 16 + r];
-                    v2 += smem[(w * SLOTS + sh) * 256 + ch * 16 + r + 8];
-                }
-                if constexpr (MODE != kActSingle) {
-                    float l1 = 0.f, l2 = 0.f;
-#pragma unroll
-                    for (int w = 0; w < kWaves; ++w) {
-                        l1 += smem[(w * SLOTS + sl) * 256 + cl * 16 + r];
-                        l2 += smem[(w * SLOTS + sl) * 256 + cl * 16 + r + 8];
-                    }
-                    v1 += l1;
-                    v2 += l2;
+                    v1 += smem[(w * SLOTS + j) * 256 + mm * 16 + r];
+                    v2 += smem[(w * SLOTS + j) * 256 + mm * 16 + r + 8];
                 }
             }
             epi.item(t0 + nwg * (valid ? j : 0), j, it, mm, r, v1, v2, valid);
