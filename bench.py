@@ -97,7 +97,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="8b_bf16_k8_ctx2048", choices=sorted(WORKLOADS))
     ap.add_argument("--p", type=float, default=0.3, help="draft corruption probability")
-    ap.add_argument("--single-kernel", type=int, default=0)
+    ap.add_argument("--seqs", type=int, default=1,
+                    help="independent sequences verified by every pass, each at the workload's context and k "
+                         "(seqs * k <= 16); the default 1 is the headline workload")
     ap.add_argument("--time-stage", default="gateup", help="stage bracketed with HIP events ('none' to disable)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--loops", action="store_true",
@@ -155,33 +157,48 @@ def main():
 
     shape_name, L0, k, seed = WORKLOADS[args.workload]
     shape = SHAPES[shape_name]
+    B = args.seqs
+    if B < 1 or B * k > A.MAX_K:
+        print(f"bench.py: --seqs {B} with k={k} does not fit the {A.MAX_K} rows of a pass", file=sys.stderr)
+        sys.exit(2)
     stream = torch.cuda.Stream()
     t0 = time.perf_counter()
     log(f"loading {shape_name} ({shape.n_params_streamed() / 1e9:.2f} G weights) ...")
-    model = load_model(shape, L0 + A.MAX_K, stream=stream.cuda_stream, progress=log)
+    model = load_model(shape, L0 + A.MAX_K, stream=stream.cuda_stream, progress=log, max_seqs=B)
     log(f"model loaded in {time.perf_counter() - t0:.1f} s")
-    model.set_option(A.OPT_SINGLE_KERNEL, args.single_kernel)
 
-    prompt = prompt_tokens(seed, L0, shape.vocab)
+    # sequence 0 is the headline sequence; further sequences get prompts of their own
+    seq_ids = list(range(B))
     t0 = time.perf_counter()
-    first = model.prefill(prompt)
-    log(f"context of {L0} tokens prefilled in {time.perf_counter() - t0:.2f} s")
-    cont = [first]
+    conts = []
+    for sq in seq_ids:
+        conts.append([model.seq_prefill(sq, prompt_tokens(seed + 1000 * sq, L0, shape.vocab))])
+    log(f"{B} context(s) of {L0} tokens prefilled in {time.perf_counter() - t0:.2f} s")
     for _ in range(k - 1):
-        cont.append(model.draft_step())
-    model.kv_rollback(L0)
-    drafts = [corrupt_drafts(seed, r, cont, args.p, shape.vocab) for r in range(args.warmup + args.steps)]
+        for sq, t in zip(seq_ids, model.draft_step_batch(seq_ids)):
+            conts[sq].append(int(t))
+    for sq in seq_ids:
+        model.seq_rollback(sq, L0)
+    n_rounds = args.warmup + args.steps
+    drafts = [[corrupt_drafts(seed + 1000 * sq, r, conts[sq], args.p, shape.vocab) for sq in seq_ids]
+              for r in range(n_rounds)]
+    ctx = [L0] * B
+
+    def one_pass(r):
+        if B == 1:
+            return model.verify(L0, drafts[r][0])[0]
+        return int(model.verify_batch(seq_ids, ctx, drafts[r])[0].sum())
 
     for r in range(args.warmup):
-        model.verify(L0, drafts[r])
+        one_pass(r)
     if args.time_stage != "none":
         model.set_option(A.OPT_TIME_STAGE, A.STAGES[args.time_stage])
     host_ms, dev_ms, accepts = [], [], []
     torch.cuda.synchronize()
     t_begin = time.perf_counter()
-    for r in range(args.warmup, args.warmup + args.steps):
+    for r in range(args.warmup, n_rounds):
         t1 = time.perf_counter()
-        n, _ = model.verify(L0, drafts[r])
+        n = one_pass(r)
         host_ms.append((time.perf_counter() - t1) * 1e3)
         dev_ms.append(model.last_pass_ms())
         accepts.append(n)
@@ -189,18 +206,18 @@ def main():
     total_s = time.perf_counter() - t_begin
     ms_per_step = total_s * 1e3 / args.steps
 
-    bytes_pass = model.weight_bytes_per_pass() + model.kv_bytes_per_pass(L0, k) \
-        + k * shape.d_model * shape.weight_elem_bytes \
-        + shape.n_layers * 2 * shape.kv_dim * shape.weight_elem_bytes * k
+    bytes_pass = model.weight_bytes_per_pass() + B * (
+        model.kv_bytes_per_pass(L0, k) + k * shape.d_model * shape.weight_elem_bytes
+        + shape.n_layers * 2 * shape.kv_dim * shape.weight_elem_bytes * k)
     gbps = bytes_pass / (ms_per_step * 1e-3) / 1e9
-    hist = np.bincount(accepts, minlength=k + 1).tolist()
+    hist = np.bincount(accepts, minlength=B * k + 1).tolist()
     out = {
         "metric": METRIC, "value": round(ms_per_step, 4), "unit": "ms", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if shape.dtype == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": args.workload, "shape": shape_name, "ctx": L0, "k": k, "corruption_p": args.p,
-                   "seed": seed, "mode": "single_kernel" if args.single_kernel else "kernel_per_stage"},
+                   "seed": seed, "seqs": B, "mode": "kernel_per_stage"},
         "latency_ms": {"host_median": round(float(np.median(host_ms)), 4),
                        "host_p10": round(float(np.percentile(host_ms, 10)), 4),
                        "host_p90": round(float(np.percentile(host_ms, 90)), 4),
@@ -216,11 +233,15 @@ def main():
         ach = b / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
         out["roofline"] = {"bound": "hbm", "kernel": args.time_stage, "achieved": round(ach, 1),
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
-                           "traffic": MEASURED_TRAFFIC.get((args.workload, args.time_stage)), "avg_launch_ms": round(avg_ms, 5), "launches": int(launches),
+                           "traffic": MEASURED_TRAFFIC.get((args.workload, args.time_stage)) if B == 1 else None, "avg_launch_ms": round(avg_ms, 5), "launches": int(launches),
                            "algorithmic_bytes_per_launch": int(b)}
     if not args.no_cpu_baseline:
         try:
-            out["cpu_baseline"] = cpu_baseline(shape, L0, k, drafts[0])
+            out["cpu_baseline"] = cpu_baseline(shape, L0, k, drafts[0][0])
+            if B > 1:       # the oracle takes the sequences one after another
+                out["cpu_baseline"]["value"] *= B
+                out["cpu_baseline"]["sample"] += f"; times {B} sequences"
+
             out["cpu_baseline"]["accepted_tok_per_s"] = round(
                 float(np.mean(accepts)) / (out["cpu_baseline"]["value"] * 1e-3), 2)
         except MemoryError as e:          # pragma: no cover

@@ -19,8 +19,10 @@
  *     different models may run concurrently from different host threads.
  *   - Token ids are int32 in [0, vocab).  Positions count tokens from 0.
  *
- * Per-model state: kv_len (tokens in the cache) and p_next, the model's greedy
- * token for position kv_len (known once the cache is non-empty).
+ * Per-sequence state: kv_len (tokens in the sequence's cache) and p_next, the
+ * model's greedy token for position kv_len (known once the cache is non-empty).
+ * A model holds max_seqs independent sequences (one by default); the calls
+ * without a sequence argument act on sequence 0.
  */
 #ifndef AMUSD_H
 #define AMUSD_H
@@ -44,6 +46,7 @@ extern "C" {
 #define AMUSD_DTYPE_BF16    1
 
 #define AMUSD_MAX_K        16   /* rows of one pass: the 16-row matrix-core tile */
+#define AMUSD_MAX_SEQS   4096   /* sequences (key-value caches) one model can hold */
 
 /* Tensor ids for amusd_model_set_tensor.  Matrices are row-major
  * [out_features, in_features] in the model's dtype (bf16 bit patterns or
@@ -67,7 +70,6 @@ enum {
 /* Options for amusd_set_option. */
 enum {
     AMUSD_OPT_KEEP_LOGITS = 0, /* 1: each pass also stores its fp32 logits (test hook), default 0 */
-    AMUSD_OPT_SINGLE_KERNEL = 1, /* 1: one persistent kernel per pass; 0: one kernel per stage */
     AMUSD_OPT_TIME_STAGE = 2    /* AMUSD_STAGE_* to bracket with HIP events in every pass, -1: none (default) */
 };
 
@@ -82,7 +84,8 @@ typedef struct amusd_model amusd_model; /* opaque, owned by the library */
 
 /* Decoder shape.  Requirements: n_q_heads / n_kv_heads is 1, 2, 4 or 8; head_dim is 64 or
  * 128; d_model, n_q_heads*head_dim and d_ffn are multiples of 32 (bf16) or 16
- * (fp32); vocab and d_ffn multiples of 16; 1 <= max_k <= AMUSD_MAX_K. */
+ * (fp32); vocab and d_ffn multiples of 16; 1 <= max_k <= AMUSD_MAX_K;
+ * 0 <= max_seqs <= AMUSD_MAX_SEQS. */
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
     int32_t max_ctx;   /* capacity of the key-value cache, in positions */
@@ -90,6 +93,7 @@ typedef struct {
     int32_t dtype;     /* AMUSD_DTYPE_* : storage type of weights and of the cache */
     float rope_theta;  /* rotary base: pair i of a head turns by pos * theta^(-2i/head_dim) */
     float rms_eps;     /* added to the mean square inside every RMSNorm */
+    int32_t max_seqs;  /* independent sequences, each with a cache of max_ctx positions; 0 means 1 */
 } amusd_config;
 
 /* All weights at once, for amusd_model_load.  The per-layer members are arrays
@@ -173,6 +177,36 @@ int amusd_kv_len(const amusd_model *m);
 /* Current p_next in *token (-1 if unknown).  */
 int amusd_get_next(const amusd_model *m, int32_t *token);
 
+/* ---- several sequences sharing one weight stream -------------------------------------------- */
+/* Not in the paper: VerifyTokens reads every weight once for k rows, so the
+ * rows of one pass may as well belong to different sequences.  Each sequence
+ * `seq` in [0, max_seqs) has its own cache, kv_len and p_next; one pass serves
+ * up to 16 rows in total.  A sequence's results are bit-identical to those of
+ * the same call made for it alone. */
+
+/* amusd_prefill / amusd_kv_rollback / amusd_set_next / amusd_kv_len /
+ * amusd_get_next for sequence `seq`.  Errors as those, plus ARG for a bad seq. */
+int amusd_seq_prefill(amusd_model *m, int32_t seq, const int32_t *tokens, int32_t n, int32_t *next_token);
+int amusd_seq_rollback(amusd_model *m, int32_t seq, int32_t new_len);
+int amusd_seq_set_next(amusd_model *m, int32_t seq, int32_t token);
+int amusd_seq_len(const amusd_model *m, int32_t seq);
+int amusd_seq_get_next(const amusd_model *m, int32_t seq, int32_t *token);
+
+/* amusd_verify for n_seq distinct sequences in one pass.  seq_ids, ctx_len, k,
+ * accept_len and next_token are host arrays of n_seq entries; drafts holds the
+ * sequences' draft tokens back to back (k[0] ids of seq_ids[0], then k[1] of
+ * seq_ids[1], ...).  Sequence i is handled exactly as amusd_verify(ctx_len[i],
+ * its drafts, k[i]) would.  Errors: ARG (n_seq outside [1,16], a repeated or
+ * bad sequence id, k[i] < 1, sum of k above max_k), RANGE, CAPACITY, TOKEN,
+ * STATE; on error no sequence has changed. */
+int amusd_verify_batch(amusd_model *m, int32_t n_seq, const int32_t *seq_ids, const int32_t *ctx_len,
+                       const int32_t *k, const int32_t *drafts, int32_t *accept_len, int32_t *next_token);
+
+/* amusd_draft_step for n_seq distinct sequences in one pass (one row each);
+ * tokens_out[i] is sequence seq_ids[i]'s new p_next.  Errors: ARG (n_seq above
+ * max_k or 16, repeated or bad id), STATE, CAPACITY. */
+int amusd_draft_step_batch(amusd_model *m, int32_t n_seq, const int32_t *seq_ids, int32_t *tokens_out);
+
 /* ---- drivers on the same steps -------------------------------------------------------------- */
 
 /* Algorithm 1 as a whole: DraftProcess and VerifyProcess run concurrently on
@@ -201,7 +235,8 @@ int amusd_generate_greedy(amusd_model *m, const int32_t *prompt, int32_t n_promp
 
 int amusd_set_option(amusd_model *m, int32_t option, int32_t value);
 
-/* fp32 logits of the last pass, rows 0..rows-1, to host memory [rows, vocab].
+/* fp32 logits of the last pass, rows 0..rows-1, to host memory [rows, vocab]
+ * (a batched pass keeps its sequences' rows back to back, in call order).
  * Needs AMUSD_OPT_KEEP_LOGITS = 1 before that pass.  Errors: ARG, STATE. */
 int amusd_get_logits(amusd_model *m, float *out, int32_t rows);
 
@@ -220,7 +255,7 @@ int amusd_last_pass_ms(amusd_model *m, float *ms);
 int amusd_stage_time(amusd_model *m, double *total_ms, int64_t *launches, int64_t *bytes_per_launch);
 
 /* Copies rows [pos0, pos0+n) of layer `layer`'s cached keys (which=0) or
- * values (which=1) to host fp32 [n_kv_heads, n, head_dim], undoing the
+ * values (which=1) of sequence 0 to host fp32 [n_kv_heads, n, head_dim], undoing the
  * library's internal layout.  Test hook. */
 int amusd_get_kv(amusd_model *m, int32_t layer, int32_t which, int32_t pos0, int32_t n, float *out);
 

@@ -7,8 +7,8 @@ library raises.
 """
 from .binding import (AmusdError, Config, Model, LoopStats, generate_async, generate_sync,
                       generate_greedy, calibration_copy, library_path, lib, TENSOR_IDS,
-                      OPT_KEEP_LOGITS, OPT_SINGLE_KERNEL, OPT_TIME_STAGE, STAGES, DTYPE_FP32, DTYPE_BF16, MAX_K)
+                      OPT_KEEP_LOGITS, OPT_TIME_STAGE, STAGES, DTYPE_FP32, DTYPE_BF16, MAX_K)
 
 __all__ = ["AmusdError", "Config", "Model", "LoopStats", "generate_async", "generate_sync",
            "generate_greedy", "calibration_copy", "library_path", "lib", "TENSOR_IDS", "OPT_KEEP_LOGITS",
-           "OPT_SINGLE_KERNEL", "OPT_TIME_STAGE", "STAGES", "DTYPE_FP32", "DTYPE_BF16", "MAX_K"]
+           "OPT_TIME_STAGE", "STAGES", "DTYPE_FP32", "DTYPE_BF16", "MAX_K"]

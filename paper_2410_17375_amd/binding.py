@@ -9,7 +9,7 @@ _LIB_PATH = os.environ.get("AMUSD_LIBRARY") or os.path.join(_HERE, "libamusd.so"
 
 DTYPE_FP32, DTYPE_BF16 = 0, 1
 MAX_K = 16
-OPT_KEEP_LOGITS, OPT_SINGLE_KERNEL, OPT_TIME_STAGE = 0, 1, 2
+OPT_KEEP_LOGITS, OPT_TIME_STAGE = 0, 2
 STAGES = {"embed": 0, "qkv": 1, "attention": 2, "attn_merge": 3, "oproj": 4, "gateup": 5, "down": 6,
           "lmhead": 7, "accept": 8}
 TENSOR_IDS = {"embed": 0, "lm_head": 1, "final_norm": 2, "wq": 3, "wk": 4, "wv": 5, "wo": 6,
@@ -32,7 +32,7 @@ class AmusdError(RuntimeError):
 class Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim",
                                          "d_ffn", "vocab", "max_ctx", "max_k", "dtype")] + \
-               [("rope_theta", C.c_float), ("rms_eps", C.c_float)]
+               [("rope_theta", C.c_float), ("rms_eps", C.c_float), ("max_seqs", C.c_int32)]
 
 
 class Weights(C.Structure):
@@ -55,7 +55,7 @@ class LoopStats(C.Structure):
 
 def _load():
     if not os.path.exists(_LIB_PATH):
-        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2410_17375_amd.build` "
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python paper_2410_17375_amd/build.py` "
                           "(there is no CPU fallback)")
     L = C.CDLL(_LIB_PATH)
     vp, i32, i32p, f32p = C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_float)
@@ -72,6 +72,13 @@ def _load():
         "amusd_set_next": (C.c_int, [vp, i32]),
         "amusd_kv_len": (C.c_int, [vp]),
         "amusd_get_next": (C.c_int, [vp, i32p]),
+        "amusd_seq_prefill": (C.c_int, [vp, i32, i32p, i32, i32p]),
+        "amusd_seq_rollback": (C.c_int, [vp, i32, i32]),
+        "amusd_seq_set_next": (C.c_int, [vp, i32, i32]),
+        "amusd_seq_len": (C.c_int, [vp, i32]),
+        "amusd_seq_get_next": (C.c_int, [vp, i32, i32p]),
+        "amusd_verify_batch": (C.c_int, [vp, i32, i32p, i32p, i32p, i32p, i32p, i32p]),
+        "amusd_draft_step_batch": (C.c_int, [vp, i32, i32p, i32p]),
         "amusd_generate_async": (C.c_int, [vp, vp, i32p, i32, i32, i32, i32p, C.POINTER(LoopStats)]),
         "amusd_generate_sync": (C.c_int, [vp, vp, i32p, i32, i32, i32, i32p, C.POINTER(LoopStats)]),
         "amusd_generate_greedy": (C.c_int, [vp, i32p, i32, i32, i32p, C.POINTER(LoopStats)]),
@@ -111,9 +118,9 @@ class Model:
     """Handle of one amusd_model.  Methods carry the C function names without the prefix."""
 
     def __init__(self, *, n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, max_ctx,
-                 max_k=MAX_K, dtype=DTYPE_BF16, rope_theta=500000.0, rms_eps=1e-5, stream=0):
+                 max_k=MAX_K, dtype=DTYPE_BF16, rope_theta=500000.0, rms_eps=1e-5, max_seqs=1, stream=0):
         self.cfg = Config(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, max_ctx, max_k,
-                          dtype, rope_theta, rms_eps)
+                          dtype, rope_theta, rms_eps, max_seqs)
         self._h = C.c_void_p()
         _check(lib.amusd_model_create(C.byref(self.cfg), C.c_void_p(stream), C.byref(self._h)))
 
@@ -171,6 +178,45 @@ class Model:
         t = C.c_int32(-1)
         _check(lib.amusd_get_next(self._h, C.byref(t)))
         return t.value
+
+    def seq_prefill(self, seq, tokens):
+        a, p = _i32(tokens)
+        nxt = C.c_int32(-1)
+        _check(lib.amusd_seq_prefill(self._h, seq, p, a.size, C.byref(nxt)))
+        return nxt.value
+
+    def seq_rollback(self, seq, new_len):
+        _check(lib.amusd_seq_rollback(self._h, seq, new_len))
+
+    def seq_set_next(self, seq, token):
+        _check(lib.amusd_seq_set_next(self._h, seq, token))
+
+    def seq_len(self, seq):
+        return lib.amusd_seq_len(self._h, seq)
+
+    def seq_get_next(self, seq):
+        t = C.c_int32(-1)
+        _check(lib.amusd_seq_get_next(self._h, seq, C.byref(t)))
+        return t.value
+
+    def verify_batch(self, seq_ids, ctx_lens, drafts):
+        """drafts: one token list per sequence.  Returns (accept_len[], next_token[])."""
+        ids, pi = _i32(seq_ids)
+        ctx, pc = _i32(ctx_lens)
+        ks, pk = _i32([len(d) for d in drafts])
+        flat, pf = _i32(np.concatenate([np.asarray(d, dtype=np.int32).ravel() for d in drafts])
+                        if len(drafts) else np.zeros(0, np.int32))
+        acc = np.full(ids.size, -1, dtype=np.int32)
+        nxt = np.full(ids.size, -1, dtype=np.int32)
+        _check(lib.amusd_verify_batch(self._h, ids.size, pi, pc, pk, pf, acc.ctypes.data_as(C.POINTER(C.c_int32)),
+                                      nxt.ctypes.data_as(C.POINTER(C.c_int32))))
+        return acc, nxt
+
+    def draft_step_batch(self, seq_ids):
+        ids, pi = _i32(seq_ids)
+        out = np.full(ids.size, -1, dtype=np.int32)
+        _check(lib.amusd_draft_step_batch(self._h, ids.size, pi, out.ctypes.data_as(C.POINTER(C.c_int32))))
+        return out
 
     def set_option(self, option, value):
         _check(lib.amusd_set_option(self._h, option, value))

@@ -11,22 +11,38 @@ constexpr int kWaves = 8;          // waves per workgroup
 constexpr int kThreads = kWaves * 64;
 constexpr int kMaxTilesPerRound = 8;
 
+constexpr int kMaxSegs = kRows;    // a pass serves at most one sequence per row
+
+// One sequence's share of a pass: rows row0 .. row0+k-1 of the tile are its
+// tokens for positions L .. L+k-1, checked against its own cache (slot).
+struct PassSeg {
+    int L;        // cache length of the sequence before the pass (ctx_len)
+    int k;        // rows of this sequence
+    int row0;     // first tile row
+    int p_ctx;    // model's greedy token for position L
+    int slot;     // which key-value cache
+    int unit0;    // first attention work unit of the sequence
+    int nchunks;  // attention chunks covering positions 0 .. L+k-1
+    int pad;
+};
+
 // Per-pass values.  They travel as kernel arguments (no device round trip
 // before the first weight load can be addressed).
 struct PassArgs {
-    int L;             // cache length before the pass (ctx_len)
-    int k;             // rows
-    int force_accept;  // 1: prefill, every row is kept
-    int keep_logits;   // 1: store fp32 logits
-    int p_ctx;         // model's greedy token for position L
-    int tokens[kRows]; // input token of each row
+    int k;              // rows of the pass, all sequences together
+    int n_seg;          // sequences in the pass
+    int force_accept;   // 1: prefill, every row is kept
+    int keep_logits;    // 1: store fp32 logits
+    int tokens[kRows];  // input token of each row
+    int row_pos[kRows]; // position of each row in its sequence
+    int row_seg[kRows]; // segment of each row
+    PassSeg seg[kMaxSegs];
 };
 
 struct PassResult {
-    int accept_len;
-    int next_token;
-    int greedy[kRows];
-    int pad[14];
+    int accept_len[kMaxSegs];   // per segment
+    int next_token[kMaxSegs];
+    int greedy[kRows];          // per row
 };
 
 struct DevLayer {
@@ -36,14 +52,15 @@ struct DevLayer {
     const uint4* wd;     // [d/16][F/KB][64]
     const float* g_attn; // [d]
     const float* g_mlp;  // [d]
-    void* kcache;        // [Hkv][ctx_pad/16][hd/4/EPL][64 lanes][EPL] elements (operand order of the score product)
-    void* vcache;        // [Hkv][ctx_pad/BK][hd/16][64 lanes][EPL] elements (matrix-core operand order)
+    void* kcache;        // [slot][Hkv][ctx_pad/16][hd/4/EPL][64 lanes][EPL] elements (operand order of the score product)
+    void* vcache;        // [slot][Hkv][ctx_pad/BK][hd/16][64 lanes][EPL] elements (matrix-core operand order)
 };
 
 struct DevModel {
     int n_layers, d, Hq, Hkv, hd, F, V, G;
     int qdim, kvdim, nqkv;
     int max_ctx, ctx_pad;
+    int n_slots;          // key-value caches (sequences the model can hold)
     int dtype;
     int chunk;            // keys per attention work unit: (8/G) runs x bpw blocks x keys-per-block
     int bpw;              // key blocks a wave walks in one attention work unit
@@ -61,14 +78,13 @@ struct DevModel {
     float* ssq;           // [d/16][16] partial sums of squares of X rows
     void* Q_hi;           // [16][qdim]
     void* Q_lo;
-    float* att_part;      // [units][G][16][hd+4]: numerator[hd], max, denominator, 2 pad
+    float* att_part;      // [units][G][16][hd+4]: numerator[hd], max, denominator, 2 pad; units <= n_slots*Hkv*max_chunks
     void* O;              // merged attention output, operand order, qdim columns
     void* H;              // SwiGLU output, operand order, F columns
     float* logits;        // [16][V]
     float* best_val;      // [lm_wgs][16]
     int* best_idx;
     PassResult* res;
-    unsigned* barrier;    // grid barrier state (single-kernel mode)
 };
 
 }  // namespace amusd

@@ -42,6 +42,19 @@ struct HostStage {          // pinned: what one pass receives from the device
 
 }  // namespace
 
+struct SeqState {            // one sequence: its cache slot's length and the model's next token
+    int kv_len = 0;
+    int p_next = -1;
+    std::vector<int> greedy_at;            // greedy_at[pos] = model's token for position pos, -1 unknown
+};
+
+struct SegReq {              // one sequence's share of a pass
+    int seq;
+    int L;
+    const int32_t* tokens;
+    int k;
+};
+
 struct amusd_model {
     amusd_config cfg{};
     hipStream_t stream = nullptr;
@@ -49,12 +62,10 @@ struct amusd_model {
     int nwg = 0;
     bool finalized = false;
     bool keep_logits = false;
-    bool single_kernel = false;
     bool logits_valid = false;
     int last_rows = 0;
-    int kv_len = 0;
-    int p_next = -1;
-    std::vector<int> greedy_at;            // greedy_at[pos] = model's token for position pos, -1 unknown
+    int n_seqs = 1;
+    std::vector<SeqState> seqs;
     std::vector<char> have;                // tensors received
     std::vector<void*> allocs;             // everything to hipFree
     std::vector<DevLayer> layers_host;
@@ -68,7 +79,7 @@ struct amusd_model {
     std::vector<hipEvent_t> tev_begin, tev_end;
     double stage_ms = 0.0;
     int64_t stage_launches = 0;
-    int last_L = 0;
+    int64_t last_positions = 0;             // cache positions the last pass's attention read, all sequences
     int esz() const { return cfg.dtype == AMUSD_DTYPE_BF16 ? 2 : 4; }
     int kb() const { return cfg.dtype == AMUSD_DTYPE_BF16 ? 32 : 16; }
     int block_keys() const { return cfg.dtype == AMUSD_DTYPE_BF16 ? 32 : 16; }
@@ -89,6 +100,7 @@ int check_config(const amusd_config* c) {
         return fail(AMUSD_E_ARG, "config: non-positive dimension");
     if (c->dtype != AMUSD_DTYPE_FP32 && c->dtype != AMUSD_DTYPE_BF16) return fail(AMUSD_E_ARG, "config: unknown dtype");
     if (c->max_k < 1 || c->max_k > AMUSD_MAX_K) return fail(AMUSD_E_ARG, "config: max_k outside [1,16]");
+    if (c->max_seqs < 0 || c->max_seqs > AMUSD_MAX_SEQS) return fail(AMUSD_E_ARG, "config: max_seqs outside [0, AMUSD_MAX_SEQS]");
     if (c->head_dim != 64 && c->head_dim != 128) return fail(AMUSD_E_ARG, "config: head_dim must be 64 or 128");
     if (c->n_q_heads % c->n_kv_heads) return fail(AMUSD_E_ARG, "config: n_q_heads not a multiple of n_kv_heads");
     {
@@ -164,19 +176,39 @@ float half_bits_to_float(uint16_t h) {      // IEEE binary16 -> float
 std::once_flag g_cfg_once;
 hipError_t g_cfg_err = hipSuccess;
 
-// Runs one pass of `k` rows at cache length L.  Tokens already validated.
-int run_pass(amusd_model* m, int L, const int32_t* tokens, int k, bool force_accept) {
+// Runs one pass: segment i feeds segs[i].k tokens of sequence segs[i].seq at cache length segs[i].L.
+// Everything is already validated (distinct sequences, lengths, capacity, tokens, row total).
+int run_pass(amusd_model* m, const SegReq* segs, int n_seg, bool force_accept) {
     HostStage* h = m->hstage;
     PassArgs P;
-    for (int j = 0; j < kRows; ++j) P.tokens[j] = j < k ? tokens[j] : 0;
-    P.L = L;
-    P.k = k;
+    std::memset(&P, 0, sizeof(P));
+    int rows = 0, units = 0;
+    int64_t positions = 0;
+    for (int i = 0; i < n_seg; ++i) {
+        const SegReq& r = segs[i];
+        PassSeg& S = P.seg[i];
+        S.L = r.L;
+        S.k = r.k;
+        S.row0 = rows;
+        S.p_ctx = m->seqs[r.seq].greedy_at[r.L];
+        S.slot = r.seq;
+        S.unit0 = units;
+        S.nchunks = (r.L + r.k + m->dm.chunk - 1) / m->dm.chunk;
+        for (int j = 0; j < r.k; ++j) {
+            P.tokens[rows + j] = r.tokens[j];
+            P.row_pos[rows + j] = r.L + j;
+            P.row_seg[rows + j] = i;
+        }
+        rows += r.k;
+        units += m->dm.Hkv * S.nchunks;
+        positions += r.L + r.k;
+    }
+    P.k = rows;
+    P.n_seg = n_seg;
     P.force_accept = force_accept ? 1 : 0;
     P.keep_logits = m->keep_logits ? 1 : 0;
-    P.p_ctx = m->greedy_at[L];
     HIP_TRY(hipEventRecord(m->ev0, m->stream));
-    HIP_TRY(launch_pass(m->dm, m->layers_host.data(), P, m->nwg, m->stream, m->single_kernel,
-                        m->timer.stage >= 0 ? &m->timer : nullptr));
+    HIP_TRY(launch_pass(m->dm, m->layers_host.data(), P, m->nwg, m->stream, m->timer.stage >= 0 ? &m->timer : nullptr));
     HIP_TRY(hipMemcpyAsync(&h->res, m->dm.res, sizeof(PassResult), hipMemcpyDeviceToHost, m->stream));
     HIP_TRY(hipEventRecord(m->ev1, m->stream));
     HIP_TRY(hipStreamSynchronize(m->stream));
@@ -189,15 +221,24 @@ int run_pass(amusd_model* m, int L, const int32_t* tokens, int k, bool force_acc
         }
         m->stage_launches += m->timer.used;
     }
-    m->last_L = L;
+    m->last_positions = positions;
     m->logits_valid = m->keep_logits;
-    m->last_rows = k;
-    for (int j = 0; j < k; ++j) m->greedy_at[L + j + 1] = h->res.greedy[j];
-    const int n = h->res.accept_len;
-    if (n < 0 || n > k) return fail(AMUSD_E_HIP, "pass returned an impossible accept_len");
-    m->kv_len = L + n;
-    m->p_next = h->res.next_token;
+    m->last_rows = rows;
+    for (int i = 0; i < n_seg; ++i)
+        if (h->res.accept_len[i] < 0 || h->res.accept_len[i] > segs[i].k)
+            return fail(AMUSD_E_HIP, "pass returned an impossible accept_len");
+    for (int i = 0; i < n_seg; ++i) {
+        SeqState& q = m->seqs[segs[i].seq];
+        for (int j = 0; j < segs[i].k; ++j) q.greedy_at[segs[i].L + j + 1] = h->res.greedy[P.seg[i].row0 + j];
+        q.kv_len = segs[i].L + h->res.accept_len[i];
+        q.p_next = h->res.next_token[i];
+    }
     return AMUSD_OK;
+}
+
+int run_pass(amusd_model* m, int seq, int L, const int32_t* tokens, int k, bool force_accept) {
+    const SegReq r{seq, L, tokens, k};
+    return run_pass(m, &r, 1, force_accept);
 }
 
 int check_tokens(const amusd_model* m, const int32_t* t, int n) {
@@ -209,6 +250,12 @@ int check_tokens(const amusd_model* m, const int32_t* t, int n) {
 int need_ready(const amusd_model* m) {
     if (!m) return fail(AMUSD_E_ARG, "null model");
     if (!m->finalized) return fail(AMUSD_E_STATE, "model not finalized");
+    return AMUSD_OK;
+}
+
+int need_seq(const amusd_model* m, int seq) {
+    if (!m) return fail(AMUSD_E_ARG, "null model");
+    if (seq < 0 || seq >= m->n_seqs) return fail(AMUSD_E_ARG, "sequence id outside [0, max_seqs)");
     return AMUSD_OK;
 }
 
@@ -271,6 +318,8 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
         D.bpw = (int)bpw;
         D.chunk = (int)(parts * bpw * BK);
     }
+    m->n_seqs = c.max_seqs > 0 ? c.max_seqs : 1;
+    D.n_slots = m->n_seqs;
     D.max_ctx = c.max_ctx;
     D.ctx_pad = (c.max_ctx + D.chunk - 1) / D.chunk * D.chunk;
     D.max_chunks = D.ctx_pad / D.chunk;
@@ -279,7 +328,8 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
     const int lm_tiles = c.vocab / 16;
     D.lm_wgs = lm_tiles < m->nwg ? lm_tiles : m->nwg;
 
-    m->greedy_at.assign((size_t)c.max_ctx + kRows + 1, -1);
+    m->seqs.resize(m->n_seqs);
+    for (SeqState& q : m->seqs) q.greedy_at.assign((size_t)c.max_ctx + kRows + 1, -1);
     m->have.assign((size_t)AMUSD_T_COUNT * (c.n_layers + 1), 0);
     m->layers_host.resize(c.n_layers);
 
@@ -296,8 +346,8 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
         ALLOC(Ly.wd, const uint4*, d * F * esz, false)
         ALLOC(Ly.g_attn, const float*, d * 4, false)
         ALLOC(Ly.g_mlp, const float*, d * 4, false)
-        ALLOC(Ly.kcache, void*, (size_t)D.Hkv * D.ctx_pad * D.hd * esz, true)
-        ALLOC(Ly.vcache, void*, (size_t)D.Hkv * D.ctx_pad * D.hd * esz, true)
+        ALLOC(Ly.kcache, void*, (size_t)D.n_slots * D.Hkv * D.ctx_pad * D.hd * esz, true)
+        ALLOC(Ly.vcache, void*, (size_t)D.n_slots * D.Hkv * D.ctx_pad * D.hd * esz, true)
     }
     ALLOC(D.layers, const DevLayer*, sizeof(DevLayer) * c.n_layers, false)
     ALLOC(D.embed, const void*, V * d * esz, false)
@@ -310,14 +360,14 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
     ALLOC(D.ssq, float*, (d / 16) * kRows * 4, true)
     ALLOC(D.Q_hi, void*, kRows * q * 4, true)
     ALLOC(D.Q_lo, void*, kRows * q * 4, true)
-    ALLOC(D.att_part, float*, (size_t)D.Hkv * D.max_chunks * D.G * kRows * (D.hd + 4) * 4, true)
+    const size_t pass_seqs = D.n_slots < kMaxSegs ? D.n_slots : kMaxSegs;
+    ALLOC(D.att_part, float*, pass_seqs * D.Hkv * D.max_chunks * D.G * kRows * (D.hd + 4) * 4, true)
     ALLOC(D.O, void*, kRows * q * 4, true)
     ALLOC(D.H, void*, kRows * F * 4, true)
     ALLOC(D.logits, float*, kRows * V * 4, true)
     ALLOC(D.best_val, float*, (size_t)m->nwg * kRows * 4, true)
     ALLOC(D.best_idx, int*, (size_t)m->nwg * kRows * 4, true)
     ALLOC(D.res, PassResult*, sizeof(PassResult), true)
-    ALLOC(D.barrier, unsigned*, 256, true)
 #undef ALLOC
     if (hipMemcpyAsync(const_cast<DevLayer*>(D.layers), m->layers_host.data(), sizeof(DevLayer) * c.n_layers,
                        hipMemcpyHostToDevice, m->stream) != hipSuccess)
@@ -476,19 +526,57 @@ int amusd_model_free(amusd_model* m) {
     return AMUSD_OK;
 }
 
-int amusd_prefill(amusd_model* m, const int32_t* tokens, int32_t n, int32_t* next_token) {
+int amusd_seq_prefill(amusd_model* m, int32_t seq, const int32_t* tokens, int32_t n, int32_t* next_token) {
     int rc = need_ready(m);
-    if (rc) return rc;
+    if (rc || (rc = need_seq(m, seq))) return rc;
     if (!tokens || n < 1) return fail(AMUSD_E_ARG, "prefill: null tokens or n < 1");
-    if ((long)m->kv_len + n > m->cfg.max_ctx) return fail(AMUSD_E_CAPACITY, "prefill: exceeds max_ctx");
+    SeqState& q = m->seqs[seq];
+    if ((long)q.kv_len + n > m->cfg.max_ctx) return fail(AMUSD_E_CAPACITY, "prefill: exceeds max_ctx");
     if ((rc = check_tokens(m, tokens, n))) return rc;
     // 16-bit models run fastest with at most 8 rows per pass (hi and lo halves share one operand fragment)
     const int chunk = m->cfg.dtype == AMUSD_DTYPE_BF16 && m->cfg.max_k > 8 ? 8 : m->cfg.max_k;
     for (int s = 0; s < n; s += chunk) {
         const int k = n - s < chunk ? n - s : chunk;
-        if ((rc = run_pass(m, m->kv_len, tokens + s, k, true))) return rc;
+        if ((rc = run_pass(m, seq, q.kv_len, tokens + s, k, true))) return rc;
     }
-    if (next_token) *next_token = m->p_next;
+    if (next_token) *next_token = q.p_next;
+    return AMUSD_OK;
+}
+
+int amusd_prefill(amusd_model* m, const int32_t* tokens, int32_t n, int32_t* next_token) {
+    return amusd_seq_prefill(m, 0, tokens, n, next_token);
+}
+
+int amusd_verify_batch(amusd_model* m, int32_t n_seq, const int32_t* seq_ids, const int32_t* ctx_len, const int32_t* k,
+                       const int32_t* drafts, int32_t* accept_len, int32_t* next_token) {
+    int rc = need_ready(m);
+    if (rc) return rc;
+    if (!seq_ids || !ctx_len || !k || !drafts || !accept_len || !next_token)
+        return fail(AMUSD_E_ARG, "verify_batch: null argument");
+    if (n_seq < 1 || n_seq > kMaxSegs) return fail(AMUSD_E_ARG, "verify_batch: n_seq outside [1, 16]");
+    SegReq segs[kMaxSegs];
+    int rows = 0;
+    for (int i = 0; i < n_seq; ++i) {
+        if ((rc = need_seq(m, seq_ids[i]))) return rc;
+        for (int j = 0; j < i; ++j)
+            if (seq_ids[j] == seq_ids[i]) return fail(AMUSD_E_ARG, "verify_batch: a sequence appears twice");
+        if (k[i] < 1) return fail(AMUSD_E_ARG, "verify_batch: k < 1");
+        const SeqState& q = m->seqs[seq_ids[i]];
+        if (ctx_len[i] < 0 || ctx_len[i] > q.kv_len) return fail(AMUSD_E_RANGE, "verify: ctx_len outside [0, kv_len]");
+        if ((long)ctx_len[i] + k[i] > m->cfg.max_ctx) return fail(AMUSD_E_CAPACITY, "verify: ctx_len + k exceeds max_ctx");
+        segs[i] = SegReq{seq_ids[i], ctx_len[i], drafts + rows, k[i]};
+        rows += k[i];
+        if (rows > m->cfg.max_k) return fail(AMUSD_E_ARG, "verify: more than max_k rows in one pass");
+    }
+    if ((rc = check_tokens(m, drafts, rows))) return rc;
+    for (int i = 0; i < n_seq; ++i)
+        if (m->seqs[seq_ids[i]].greedy_at[ctx_len[i]] < 0)
+            return fail(AMUSD_E_STATE, "verify: the model's token for position ctx_len is unknown");
+    if ((rc = run_pass(m, segs, n_seq, false))) return rc;
+    for (int i = 0; i < n_seq; ++i) {
+        accept_len[i] = m->hstage->res.accept_len[i];
+        next_token[i] = m->hstage->res.next_token[i];
+    }
     return AMUSD_OK;
 }
 
@@ -498,57 +586,82 @@ int amusd_verify(amusd_model* m, int32_t ctx_len, const int32_t* draft, int32_t 
     if (rc) return rc;
     if (!draft || !accept_len || !next_token) return fail(AMUSD_E_ARG, "verify: null argument");
     if (k < 1 || k > m->cfg.max_k) return fail(AMUSD_E_ARG, "verify: k outside [1, max_k]");
-    if (ctx_len < 0 || ctx_len > m->kv_len) return fail(AMUSD_E_RANGE, "verify: ctx_len outside [0, kv_len]");
-    if ((long)ctx_len + k > m->cfg.max_ctx) return fail(AMUSD_E_CAPACITY, "verify: ctx_len + k exceeds max_ctx");
-    if ((rc = check_tokens(m, draft, k))) return rc;
-    if (m->greedy_at[ctx_len] < 0) return fail(AMUSD_E_STATE, "verify: the model's token for position ctx_len is unknown");
-    if ((rc = run_pass(m, ctx_len, draft, k, false))) return rc;
-    *accept_len = m->hstage->res.accept_len;
-    *next_token = m->hstage->res.next_token;
+    const int32_t seq = 0;
+    return amusd_verify_batch(m, 1, &seq, &ctx_len, &k, draft, accept_len, next_token);
+}
+
+int amusd_draft_step_batch(amusd_model* m, int32_t n_seq, const int32_t* seq_ids, int32_t* tokens_out) {
+    int rc = need_ready(m);
+    if (rc) return rc;
+    if (!seq_ids || !tokens_out) return fail(AMUSD_E_ARG, "draft_step: null argument");
+    if (n_seq < 1 || n_seq > kMaxSegs || n_seq > m->cfg.max_k) return fail(AMUSD_E_ARG, "draft_step: n_seq outside [1, max_k]");
+    SegReq segs[kMaxSegs];
+    int32_t toks[kMaxSegs];
+    for (int i = 0; i < n_seq; ++i) {
+        if ((rc = need_seq(m, seq_ids[i]))) return rc;
+        for (int j = 0; j < i; ++j)
+            if (seq_ids[j] == seq_ids[i]) return fail(AMUSD_E_ARG, "draft_step: a sequence appears twice");
+        const SeqState& q = m->seqs[seq_ids[i]];
+        if (q.p_next < 0) return fail(AMUSD_E_STATE, "draft_step: p_next unknown");
+        if (q.kv_len + 1 > m->cfg.max_ctx) return fail(AMUSD_E_CAPACITY, "draft_step: cache full");
+        toks[i] = q.p_next;
+        segs[i] = SegReq{seq_ids[i], q.kv_len, &toks[i], 1};
+    }
+    if ((rc = run_pass(m, segs, n_seq, true))) return rc;
+    for (int i = 0; i < n_seq; ++i) tokens_out[i] = m->seqs[seq_ids[i]].p_next;
     return AMUSD_OK;
 }
 
 int amusd_draft_step(amusd_model* m, int32_t* token_out) {
-    int rc = need_ready(m);
+    const int32_t seq = 0;
+    return amusd_draft_step_batch(m, 1, &seq, token_out);
+}
+
+int amusd_seq_rollback(amusd_model* m, int32_t seq, int32_t new_len) {
+    int rc = need_seq(m, seq);
     if (rc) return rc;
-    if (!token_out) return fail(AMUSD_E_ARG, "draft_step: null argument");
-    if (m->p_next < 0) return fail(AMUSD_E_STATE, "draft_step: p_next unknown");
-    if (m->kv_len + 1 > m->cfg.max_ctx) return fail(AMUSD_E_CAPACITY, "draft_step: cache full");
-    const int32_t t = m->p_next;
-    if ((rc = run_pass(m, m->kv_len, &t, 1, true))) return rc;
-    *token_out = m->p_next;
+    SeqState& q = m->seqs[seq];
+    if (new_len < 0 || new_len > q.kv_len) return fail(AMUSD_E_RANGE, "rollback: new_len outside [0, kv_len]");
+    q.kv_len = new_len;
+    q.p_next = q.greedy_at[new_len];
     return AMUSD_OK;
 }
 
-int amusd_kv_rollback(amusd_model* m, int32_t new_len) {
-    if (!m) return fail(AMUSD_E_ARG, "null model");
-    if (new_len < 0 || new_len > m->kv_len) return fail(AMUSD_E_RANGE, "rollback: new_len outside [0, kv_len]");
-    m->kv_len = new_len;
-    m->p_next = m->greedy_at[new_len];
-    return AMUSD_OK;
-}
+int amusd_kv_rollback(amusd_model* m, int32_t new_len) { return amusd_seq_rollback(m, 0, new_len); }
 
-int amusd_set_next(amusd_model* m, int32_t token) {
-    if (!m) return fail(AMUSD_E_ARG, "null model");
+int amusd_seq_set_next(amusd_model* m, int32_t seq, int32_t token) {
+    int rc = need_seq(m, seq);
+    if (rc) return rc;
     if (token < 0 || token >= m->cfg.vocab) return fail(AMUSD_E_TOKEN, "set_next: token id outside [0, vocab)");
-    m->p_next = token;
-    m->greedy_at[m->kv_len] = token;
+    SeqState& q = m->seqs[seq];
+    q.p_next = token;
+    q.greedy_at[q.kv_len] = token;
     return AMUSD_OK;
 }
 
-int amusd_kv_len(const amusd_model* m) { return m ? m->kv_len : fail(AMUSD_E_ARG, "null model"); }
+int amusd_set_next(amusd_model* m, int32_t token) { return amusd_seq_set_next(m, 0, token); }
 
-int amusd_get_next(const amusd_model* m, int32_t* token) {
-    if (!m || !token) return fail(AMUSD_E_ARG, "null argument");
-    *token = m->p_next;
+int amusd_seq_len(const amusd_model* m, int32_t seq) {
+    const int rc = need_seq(m, seq);
+    return rc ? rc : m->seqs[seq].kv_len;
+}
+
+int amusd_kv_len(const amusd_model* m) { return amusd_seq_len(m, 0); }
+
+int amusd_seq_get_next(const amusd_model* m, int32_t seq, int32_t* token) {
+    if (!token) return fail(AMUSD_E_ARG, "null argument");
+    const int rc = need_seq(m, seq);
+    if (rc) return rc;
+    *token = m->seqs[seq].p_next;
     return AMUSD_OK;
 }
+
+int amusd_get_next(const amusd_model* m, int32_t* token) { return amusd_seq_get_next(m, 0, token); }
 
 int amusd_set_option(amusd_model* m, int32_t option, int32_t value) {
     if (!m) return fail(AMUSD_E_ARG, "null model");
     switch (option) {
         case AMUSD_OPT_KEEP_LOGITS: m->keep_logits = value != 0; return AMUSD_OK;
-        case AMUSD_OPT_SINGLE_KERNEL: m->single_kernel = value != 0; return AMUSD_OK;
         case AMUSD_OPT_TIME_STAGE: {
             if (value < -1 || value >= AMUSD_STAGE_COUNT) return fail(AMUSD_E_ARG, "unknown stage");
             if (value >= 0 && m->tev_begin.empty()) {
@@ -602,7 +715,7 @@ int amusd_stage_time(amusd_model* m, double* total_ms, int64_t* launches, int64_
     int64_t b = 0;
     switch (m->timer.stage) {
         case AMUSD_STAGE_QKV: b = d * (q + 2 * kv) * e; break;
-        case AMUSD_STAGE_ATTENTION: b = 2 * kv * e * ((int64_t)m->last_L + m->last_rows); break;
+        case AMUSD_STAGE_ATTENTION: b = 2 * kv * e * m->last_positions; break;
         case AMUSD_STAGE_OPROJ: b = q * d * e; break;
         case AMUSD_STAGE_GATEUP: b = 2 * d * F * e; break;
         case AMUSD_STAGE_DOWN: b = d * F * e; break;
@@ -685,7 +798,7 @@ struct ModelBackend final : StepBackend {
     int draft_step(int32_t* t) override { return amusd_draft_step(m, t); }
     int rollback(int n) override { return amusd_kv_rollback(m, n); }
     int set_next(int32_t t) override { return amusd_set_next(m, t); }
-    int kv_len() const override { return m->kv_len; }
+    int kv_len() const override { return m->seqs[0].kv_len; }
     int max_ctx() const override { return m->cfg.max_ctx; }
     int vocab() const override { return m->cfg.vocab; }
 };

@@ -445,7 +445,8 @@ struct EpiQKV {
     const DevModel& M;
     const DevLayer& Ly;
     float* rstd;         // LDS
-    int L, k_rows;
+    const PassArgs& P;
+    int k_rows;
     RstdPrefetch pre;
     float pc[2], ps[2];
     __device__ __forceinline__ void prefetch(int t0, int stride, int nt) {
@@ -459,8 +460,9 @@ struct EpiQKV {
             const int tile = t0 + stride * j;
             if (j < nt && mm < k_rows && tile < rot_tiles) {
                 const int i = (tile % tph) * 8 + r;           // q and k sections both start at a head boundary
-                pc[it] = M.rope_cos[(size_t)(L + mm) * (hd / 2) + i];
-                ps[it] = M.rope_sin[(size_t)(L + mm) * (hd / 2) + i];
+                const int pos = P.row_pos[mm];
+                pc[it] = M.rope_cos[(size_t)pos * (hd / 2) + i];
+                ps[it] = M.rope_sin[(size_t)pos * (hd / 2) + i];
             }
         }
     }
@@ -470,7 +472,8 @@ struct EpiQKV {
         const int hd = M.hd, tph = hd / 16;
         const float sc = rstd[mm];
         const float x1 = v1 * sc, x2 = v2 * sc;
-        const int pos = L + mm;
+        const int pos = P.row_pos[mm];
+        const size_t slot_base = (size_t)P.seg[P.row_seg[mm]].slot * M.Hkv * M.ctx_pad * hd;   // elements, K and V alike
         const int qt = M.qdim / 16, kt = M.kvdim / 16;
         if (tile < qt + kt) {
             const bool isq = tile < qt;
@@ -483,7 +486,7 @@ struct EpiQKV {
                 store_act<DT>(M.Q_hi, M.Q_lo, o, y1);
                 store_act<DT>(M.Q_hi, M.Q_lo, o + hd / 2, y2);
             } else {
-                const size_t hb = (size_t)head * M.ctx_pad * hd;
+                const size_t hb = slot_base + (size_t)head * M.ctx_pad * hd;
                 const size_t o1 = hb + kcache_index<DT>(hd, pos, i), o2 = hb + kcache_index<DT>(hd, pos, i + hd / 2);
                 if constexpr (DT::HAS_LO) {
                     reinterpret_cast<uint16_t*>(Ly.kcache)[o1] = (uint16_t)DT::att_bits(y1);
@@ -500,8 +503,8 @@ struct EpiQKV {
             const int b = pos / BK, q = pos % BK;
             const int e = (q / 16) * 4 + (q % 4), gg = (q % 16) / 4;
             const size_t blk = ((size_t)head * (M.ctx_pad / BK) + b) * tph + j;
-            const size_t o1 = (blk * 64 + gg * 16 + r) * DT::EPL + e;
-            const size_t o2 = (blk * 64 + gg * 16 + r + 8) * DT::EPL + e;
+            const size_t o1 = slot_base + (blk * 64 + gg * 16 + r) * DT::EPL + e;
+            const size_t o2 = slot_base + (blk * 64 + gg * 16 + r + 8) * DT::EPL + e;
             if constexpr (DT::HAS_LO) {
                 reinterpret_cast<uint16_t*>(Ly.vcache)[o1] = (uint16_t)DT::att_bits(x1);
                 reinterpret_cast<uint16_t*>(Ly.vcache)[o2] = (uint16_t)DT::att_bits(x2);
@@ -621,7 +624,7 @@ __device__ __forceinline__ void stage_embed(const DevModel& M, const float* __re
 template <class DT>
 __device__ __forceinline__ void stage_qkv(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int nwg,
                                           float* smem) {
-    EpiQKV<DT> epi{M, Ly, smem + kOffRstd, P.L, P.k, {}, {}, {}};
+    EpiQKV<DT> epi{M, Ly, smem + kOffRstd, P, P.k, {}, {}, {}};
     epi.pre.begin(M);
     gemm_stage<DT>(Ly.wqkv, M.nqkv / 16, M.d / DT::KB, M.A, P.k, wg, nwg, epi, smem);
 }
@@ -659,9 +662,10 @@ __device__ __forceinline__ void stage_lmhead(const DevModel& M, const PassArgs& 
     }
 }
 
-// Causal grouped-query attention of the k rows against keys 0 .. L+k-1.
-// Work unit = (kv head, chunk of 8 key blocks; a block is 32 keys bf16 / 16 keys
-// fp32).  Wave w of the workgroup serves query head w % G of the group and the
+// Causal grouped-query attention: every sequence of the pass has its k rows
+// checked against keys 0 .. L+k-1 of its own cache.
+// Work unit = (sequence, kv head, chunk of 8 key blocks; a block is 32 keys bf16 / 16 keys
+// fp32); tile rows of other sequences are masked out of the unit.  Wave w of the workgroup serves query head w % G of the group and the
 // w / G -th run of G consecutive blocks, walking them in order with a running
 // softmax (max, denominator, numerator) in registers; the next block's K and V
 // fragments are fetched while the current one is used.  Scores are computed
@@ -680,11 +684,8 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
     constexpr int HT = HD / 16;              // 16-wide head_dim tiles
     constexpr int BK = DT::BLOCK_KEYS, TPB = DT::TPB;
     constexpr int HDP = HD + kAttPad;
-    const int L = P.L, k = P.k;
-    const int T = L + k;
-    const int CS = M.chunk;                  // = parts * bpw * BK
-    const int nchunks = (T + CS - 1) / CS;
-    const int units = M.Hkv * nchunks;
+    const int last = P.n_seg - 1;
+    const int units = P.seg[last].unit0 + M.Hkv * P.seg[last].nchunks;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
     const int G = M.G, parts = kWaves / G, bpw = M.bpw;
@@ -695,12 +696,19 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
     const uint4 zero4 = uint4{0, 0, 0, 0};
     AMUSD_TP(2, wg, 0);
     for (int u = wg; u < units; u += nwg) {
-        const int kvh = u / nchunks, c = u % nchunks;
+        int si = 0;
+        while (si < last && u >= P.seg[si + 1].unit0) ++si;
+        const PassSeg& S = P.seg[si];
+        const int L = S.L, k = S.k, row0 = S.row0, T = L + k, nchunks = S.nchunks;
+        const int ul = u - S.unit0;
+        const int kvh = ul / nchunks, c = ul % nchunks;
+        const size_t slot_frags = (size_t)S.slot * M.Hkv * M.ctx_pad * HD / DT::EPL;   // 16-byte fragments per cache
+        const bool mine = m >= row0 && m < row0 + k;     // tile row m belongs to this sequence
         const int head = kvh * G + hq;
         const int b0 = (c * parts + part) * bpw;       // first block of this wave's run
         uint4 qh[FR], ql[FR];
         {
-            const int mq = m < k ? m : k - 1;          // rows >= k mirror row k-1; never written out
+            const int mq = mine ? m : row0;            // other rows mirror row0; fully masked, never written out
             const size_t q0 = (size_t)mq * M.qdim + head * HD + g * (HD / 4);
 #pragma unroll
             for (int i = 0; i < FR; ++i) {
@@ -712,13 +720,14 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
         uint4 kf[TPB][FR], vf[HT];
         auto load_block = [&](int b, uint4 (&kd)[TPB][FR], uint4 (&vd)[HT]) {
             const int bb = b < nblk ? b : nblk - 1;    // stay inside the cache allocation
-            const uint4* kb = reinterpret_cast<const uint4*>(Ly.kcache) +
+            const uint4* kb = reinterpret_cast<const uint4*>(Ly.kcache) + slot_frags +
                               ((size_t)kvh * (M.ctx_pad / 16) + (size_t)bb * TPB) * FR * 64 + lane;
 #pragma unroll
             for (int t = 0; t < TPB; ++t)
 #pragma unroll
                 for (int i = 0; i < FR; ++i) kd[t][i] = kb[(t * FR + i) * 64];
-            const uint4* vb = reinterpret_cast<const uint4*>(Ly.vcache) + (((size_t)kvh * nblk + bb) * HT) * 64 + lane;
+            const uint4* vb = reinterpret_cast<const uint4*>(Ly.vcache) + slot_frags +
+                              (((size_t)kvh * nblk + bb) * HT) * 64 + lane;
 #pragma unroll
             for (int j = 0; j < HT; ++j) vd[j] = vb[j * 64];
         };
@@ -746,7 +755,8 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int key = p0 + t * 16 + g * 4 + e;
-                    sv[t][e] = key <= L + m ? sc[e] * M.att_scale : -INFINITY;   // causal: row m sees keys 0..L+m
+                    // causal: the sequence's j-th row (tile row row0+j) sees keys 0..L+j
+                    sv[t][e] = mine && key <= L + m - row0 ? sc[e] * M.att_scale : -INFINITY;
                     mx = fmaxf(mx, sv[t][e]);
                 }
             }
@@ -810,7 +820,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
         // merge the runs of each head in run order; item = (head, row, 4 consecutive head_dim entries)
         for (int x = tid; x < G * kRows * (HD / 4); x += kThreads) {
             const int c4 = x % (HD / 4), mm = (x / (HD / 4)) % kRows, hh = x / (kRows * (HD / 4));
-            if (mm >= k) continue;
+            if (mm < row0 || mm >= row0 + k) continue;
             float Mx = -INFINITY;
             for (int pp = 0; pp < parts; ++pp) Mx = fmaxf(Mx, partML[((hh * parts + pp) * kRows + mm) * 2]);
             float den = 0.f;
@@ -838,9 +848,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
 // head_dim each.
 template <class DT, int HD>
 __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassArgs& P, int wg, int nwg) {
-    const int L = P.L, k = P.k;
-    const int T = L + k, CS = M.chunk;
-    const int nchunks = (T + CS - 1) / CS;
+    const int k = P.k, CS = M.chunk;
     const int lane = threadIdx.x & 63;
     const int wpb = blockDim.x >> 6;
     const int gw = wg * wpb + (threadIdx.x >> 6), nw = nwg * wpb;
@@ -849,8 +857,9 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassAr
     for (int x = gw; x < M.Hq * k; x += nw) {
         const int head = x / k, mm = x % k;
         const int kvh = head / M.G, hq = head % M.G;
-        const int nch = (L + mm) / CS + 1;            // chunks holding keys this row can see
-        const float* base = M.att_part + (((size_t)kvh * nchunks * M.G + hq) * kRows + mm) * ROW;
+        const PassSeg& S = P.seg[P.row_seg[mm]];
+        const int nch = P.row_pos[mm] / CS + 1;       // chunks holding keys this row can see
+        const float* base = M.att_part + ((((size_t)S.unit0 + (size_t)kvh * S.nchunks) * M.G + hq) * kRows + mm) * ROW;
         const size_t cstride = (size_t)M.G * kRows * ROW;
         float Mrun = -INFINITY, den = 0.f, num[PER];
 #pragma unroll
@@ -908,9 +917,9 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassAr
 }
 
 // Arg-max across workgroups by wave shuffles (wave r reduces row r), then the
-// mismatch test of Algorithm 1 on wave 0: target = [p_ctx, g[0], .., g[k-2]],
-// accept the longest prefix with draft == target, emit the model's own token at
-// the first mismatch (or g[k-1] when all match).  One workgroup of 16 waves.
+// mismatch test of Algorithm 1 on wave 0, per sequence: target = [p_ctx, g[0], .., g[k-2]]
+// over the sequence's rows, accept the longest prefix with draft == target, emit the
+// model's own token at the first mismatch (or g[k-1] when all match).  One workgroup of 16 waves.
 __device__ __forceinline__ void stage_accept(const DevModel& M, const PassArgs& P, int* sg) {
     const int lane = threadIdx.x & 63, row = threadIdx.x >> 6;
     const int k = P.k;
@@ -935,17 +944,23 @@ __device__ __forceinline__ void stage_accept(const DevModel& M, const PassArgs& 
     if (row != 0) return;
     const int myg = lane < kRows ? sg[lane] : -1;
     if (lane < kRows) M.res->greedy[lane] = myg;
-    // lane j holds g[j]; target[j] = j ? g[j-1] : p_ctx
+    // lane r holds g[r]; for the sequence's first row the target is its p_ctx, else the previous row's g
+    const int rl = lane < kRows ? lane : 0;
+    const PassSeg& Sr = P.seg[P.row_seg[rl]];
     const int prev = __shfl_up(myg, 1, 64);
-    const int target = lane == 0 ? P.p_ctx : prev;
-    const bool match = lane < k && (P.force_accept || P.tokens[lane < kRows ? lane : 0] == target);
+    const int target = rl == Sr.row0 ? Sr.p_ctx : prev;
+    const bool match = lane < k && (P.force_accept || P.tokens[rl] == target);
     const unsigned long long ball = __ballot(match);
-    const int n = __ffsll((long long)~ball) - 1;          // first lane that does not match (lanes >= k never match)
-    const int gk = __shfl(myg, k - 1, 64);
-    const int nxt_t = __shfl(target, n < k ? n : 0, 64);
-    if (lane == 0) {
-        M.res->accept_len = n;
-        M.res->next_token = n < k ? nxt_t : gk;
+    // lane s now serves segment s
+    const int sl = lane < P.n_seg ? lane : 0;
+    const PassSeg& S = P.seg[sl];
+    const unsigned long long seg_match = (ball >> S.row0) & ((1ull << S.k) - 1ull);
+    const int n = __ffsll((long long)~seg_match) - 1;                       // first row of the segment that does not match; k if none
+    const int gk = __shfl(myg, S.row0 + S.k - 1, 64);
+    const int nxt_t = __shfl(target, S.row0 + (n < S.k ? n : 0), 64);
+    if (lane < P.n_seg) {
+        M.res->accept_len[lane] = n;
+        M.res->next_token[lane] = n < S.k ? nxt_t : gk;
     }
 }
 
@@ -1067,8 +1082,7 @@ static hipError_t launch_pass_t(const DevModel& M, const DevLayer* Ls, const Pas
                                 StageTimer* tm) {
     const dim3 blk(kThreads);
     const int embed_wgs = (M.d / 16 + 3) / 4 < nwg ? (M.d / 16 + 3) / 4 : nwg;
-    const int T = P.L + P.k;
-    const int att_units = M.Hkv * ((T + M.chunk - 1) / M.chunk);
+    const int att_units = P.seg[P.n_seg - 1].unit0 + M.Hkv * P.seg[P.n_seg - 1].nchunks;
     const int att_wgs = att_units < nwg ? att_units : nwg;
     const int merge_wgs = M.Hq * P.k;      // one wave each
     const int qkv_wgs = M.nqkv / 16 < nwg ? M.nqkv / 16 : nwg;
@@ -1110,8 +1124,7 @@ static hipError_t launch_pass_t(const DevModel& M, const DevLayer* Ls, const Pas
 }
 
 hipError_t launch_pass(const DevModel& M, const DevLayer* Ls, const PassArgs& P, int nwg, hipStream_t stream,
-                       bool single_kernel, StageTimer* tm) {
-    (void)single_kernel;
+                       StageTimer* tm) {
     if (M.dtype)
         return M.hd == 128 ? launch_pass_t<BF16, 128>(M, Ls, P, nwg, stream, tm)
                            : launch_pass_t<BF16, 64>(M, Ls, P, nwg, stream, tm);

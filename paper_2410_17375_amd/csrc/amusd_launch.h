@@ -32,6 +32,6 @@ hipError_t launch_copy(uint4* dst, const uint4* src, size_t n, hipStream_t strea
 
 // Enqueues one whole pass (all stages) on the stream.
 hipError_t launch_pass(const DevModel& M, const DevLayer* layers_host, const PassArgs& P, int nwg, hipStream_t stream,
-                       bool single_kernel, StageTimer* timer);
+                       StageTimer* timer);
 
 }  // namespace amusd

@@ -14,8 +14,11 @@ HEADER = os.path.join(ROOT, "include", "amusd.h")
 def A():
     lib = os.path.join(ROOT, "paper_2410_17375_amd", "libamusd.so")
     if not os.path.exists(lib):
-        from paper_2410_17375_amd.build import build
-        build(verbose=False)
+        import importlib.util                     # by path: importing the package needs the library
+        spec = importlib.util.spec_from_file_location("_amusd_build", os.path.join(ROOT, "paper_2410_17375_amd", "build.py"))
+        mod = importlib.util.module_from_spec(spec)
+        spec.loader.exec_module(mod)
+        mod.build(verbose=False)
     import paper_2410_17375_amd as pkg
     return pkg
 
@@ -50,6 +53,10 @@ def test_error_strings_and_null_arguments(A):
     assert L.amusd_kv_len(None) == -1
     assert L.amusd_kv_rollback(None, 0) == -1
     assert L.amusd_verify(None, 0, None, 1, None, None) == -1
+    assert L.amusd_verify_batch(None, 1, None, None, None, None, None, None) == -1
+    assert L.amusd_draft_step_batch(None, 1, None, None) == -1
+    assert L.amusd_seq_len(None, 0) == -1
+    assert L.amusd_seq_rollback(None, 0, 0) == -1
     assert L.amusd_model_finalize(None) == -1
     assert L.amusd_model_free(None) == 0
     assert L.amusd_model_create(None, None, None) == -1
@@ -60,7 +67,7 @@ def test_bad_configs_are_rejected_before_any_device_work(A):
     good = dict(n_layers=1, d_model=64, n_q_heads=2, n_kv_heads=1, head_dim=64, d_ffn=128, vocab=64, max_ctx=8)
     bad = [dict(head_dim=48), dict(n_kv_heads=3), dict(n_q_heads=3, n_kv_heads=1), dict(d_model=40),
            dict(vocab=50), dict(max_k=17), dict(max_k=0), dict(dtype=5), dict(n_layers=0), dict(max_ctx=0),
-           dict(rope_theta=0.0), dict(d_ffn=100)]
+           dict(rope_theta=0.0), dict(d_ffn=100), dict(max_seqs=-1), dict(max_seqs=5000)]
     for change in bad:
         with pytest.raises(A.AmusdError) as e:
             A.Model(**{**good, **change})

@@ -49,7 +49,7 @@ def _gpu():
 def model_8b():
     A, load_model, torch = _gpu()
     say("loading the 8B-shape model")
-    m = load_model(SHAPES["8b"], 2048 + 64, progress=None)
+    m = load_model(SHAPES["8b"], 2048 + 64, progress=None, max_seqs=2)
     m.set_option(A.OPT_KEEP_LOGITS, 1)
     yield A, m
     m.free()
@@ -161,6 +161,75 @@ def test_8b_k_row_pass_equals_single_row_passes_and_rollback(model_8b):
     m.kv_rollback(L0 + 3)
     m.prefill(toks[3:8])
     assert np.array_equal(m.get_logits(5), za[3:8])
+
+
+def test_8b_two_sequences_share_one_pass(model_8b):
+    """Two sequences at context 2048, 8 draft rows each, in one 16-row pass: each against the stored
+    oracle values of its own window; bit for bit the logits of the same window verified alone; and a
+    sequence at another context length in the same pass."""
+    A, m = model_8b
+    path = os.path.join(GOLDEN, "8b_k8_ctx2048.json")
+    if not os.path.exists(path):
+        pytest.skip("stored oracle values missing: run tests/golden/make_golden.py 8b_k8_ctx2048")
+    gold = json.load(open(path))
+    shape, L0, k = SHAPES["8b"], gold["ctx"], gold["k"]
+    prompt = prompt_tokens(gold["seed"], L0, shape.vocab)
+    c = gold["continuation"]
+    ids = np.array(gold["sampled_ids"])
+    say("8B: prefilling both sequences")
+    for sq in (0, 1):
+        m.seq_rollback(sq, 0)
+        m.seq_prefill(sq, prompt)
+    wins = gold["windows"]
+    for a in range(len(wins)):
+        b = (a + 1) % len(wins)
+        drafts = [np.array(wins[a]["draft"], dtype=np.int32), np.array(wins[b]["draft"], dtype=np.int32)]
+        for sq in (0, 1):
+            m.seq_rollback(sq, L0)
+            m.seq_set_next(sq, c[0])
+        acc, nxt = m.verify_batch([0, 1], [L0, L0], drafts)
+        z = m.get_logits(2 * k).copy()
+        gg = m.get_greedy(2 * k).copy()
+        for sq, w in ((0, wins[a]), (1, wins[b])):
+            flagged = []
+            for j, row in enumerate(w["rows"]):
+                zr = z[sq * k + j]
+                e = max(np.abs(zr[row["top_ids"]] - np.array(row["top_logits"])).max(),
+                        np.abs(zr[ids] - np.array(row["sampled_logits"])).max())
+                assert e <= TOL, f"windows {a},{b} seq {sq} row {j}: logit error {e:.3e}"
+                if row["margin"] < TOL:
+                    flagged.append(j)
+                else:
+                    assert gg[sq * k + j] == row["argmax"]
+            if not any(j <= min(w["accept_len"], k - 1) for j in flagged):
+                assert (acc[sq], nxt[sq]) == (w["accept_len"], w["next_token"]), (a, b, sq)
+                assert m.seq_len(sq) == L0 + w["accept_len"]
+        # the same windows verified alone (8-row passes): same bits
+        for sq in (0, 1):
+            m.seq_rollback(sq, L0)
+            m.seq_set_next(sq, c[0])
+            a1, n1 = m.verify_batch([sq], [L0], [drafts[sq]])
+            assert (a1[0], n1[0]) == (acc[sq], nxt[sq])
+            assert np.array_equal(m.get_logits(k).view(np.uint32), z[sq * k:(sq + 1) * k].view(np.uint32)), (a, sq)
+        say(f"8B two-sequence pass, windows {wins[a]['name']}+{wins[b]['name']}: accept_len {list(acc)}")
+    # different context lengths in one pass: sequence 1 cut back to 1000 tokens and fed the prompt's own
+    # next 5 tokens, sequence 0 at 2048 with 8 drafts
+    m.seq_rollback(1, 1000)
+    m.seq_rollback(0, L0)
+    m.seq_set_next(0, c[0])
+    d0, d1 = np.array(wins[0]["draft"], dtype=np.int32), prompt[1000:1005]
+    acc, nxt = m.verify_batch([1, 0], [1000, L0], [d1, d0])
+    z = m.get_logits(13).copy()
+    m.seq_rollback(1, 1000)
+    a1, n1 = m.verify_batch([1], [1000], [d1])
+    assert (a1[0], n1[0]) == (acc[0], nxt[0])
+    assert np.array_equal(m.get_logits(5).view(np.uint32), z[:5].view(np.uint32))
+    m.seq_rollback(0, L0)
+    m.seq_set_next(0, c[0])
+    a0, n0 = m.verify_batch([0], [L0], [d0])
+    assert (a0[0], n0[0]) == (acc[1], nxt[1]) == (wins[0]["accept_len"], wins[0]["next_token"]) or \
+        any(r["margin"] < TOL for r in wins[0]["rows"])
+    assert np.array_equal(m.get_logits(8).view(np.uint32), z[5:].view(np.uint32))
 
 
 def test_full_asynchronous_loop_reproduces_greedy_sequence():
