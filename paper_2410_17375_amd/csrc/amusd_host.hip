@@ -309,17 +309,19 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
     D.F = c.d_ffn; D.V = c.vocab; D.G = c.n_q_heads / c.n_kv_heads;
     D.qdim = c.n_q_heads * c.head_dim; D.kvdim = c.n_kv_heads * c.head_dim; D.nqkv = D.qdim + 2 * D.kvdim;
     D.dtype = c.dtype;
-    {   // attention work units: about one per CU at full context, each wave walking bpw key blocks
+    m->n_seqs = c.max_seqs > 0 ? c.max_seqs : 1;
+    D.n_slots = m->n_seqs;
+    {   // attention work units: about one per CU when the sequences of a pass (two, for a model that holds
+        // several) are at full context, each wave walking bpw key blocks
         const int parts = kWaves / D.G;
-        const int per_kvh = m->nwg / D.Hkv > 0 ? m->nwg / D.Hkv : 1;
+        const int share = D.Hkv * (m->n_seqs > 1 ? 2 : 1);
+        const int per_kvh = m->nwg / share > 0 ? m->nwg / share : 1;
         const long unit_min = (long)parts * BK;
         long bpw = (c.max_ctx + per_kvh * unit_min - 1) / (per_kvh * unit_min);
         if (bpw < 1) bpw = 1;
         D.bpw = (int)bpw;
         D.chunk = (int)(parts * bpw * BK);
     }
-    m->n_seqs = c.max_seqs > 0 ? c.max_seqs : 1;
-    D.n_slots = m->n_seqs;
     D.max_ctx = c.max_ctx;
     D.ctx_pad = (c.max_ctx + D.chunk - 1) / D.chunk * D.chunk;
     D.max_chunks = D.ctx_pad / D.chunk;
