@@ -214,3 +214,45 @@ def test_error_codes_and_edges():
     assert n in (0, 1) and 0 <= nxt < shape.vocab
     g.kv_rollback(0)
     assert g.kv_len() == 0 and g.get_next() == -1
+
+
+@pytest.mark.parametrize("p", [0.1, 0.3, 0.6])
+def test_accept_length_follows_the_first_corrupted_draft(p):
+    """Fixed context, the oracle's greedy continuation corrupted with probability p per position: the
+    pass must accept exactly up to the first changed token, and over many rounds the accept lengths
+    follow the closed form P(n=j) = (1-p')^j p' (j<k), P(n=k) = (1-p')^k with p' = p(1-1/V)."""
+    from oracle import Decoder, OracleStepper, greedy_autoregressive
+    from scipy.stats import chisquare
+    A, load_model = _gpu()
+    shape = SHAPES["tiny_gqa_bf16"]
+    store = WeightStore(shape)
+    k, L0, rounds = 8, 48, 400
+    g = load_model(shape, 96, store=store)
+    prompt = prompt_tokens(12, L0, shape.vocab)    # a prompt whose greedy path has no near-tie in the window
+    o = OracleStepper(Decoder(shape, store, 96))
+    cont = greedy_autoregressive(o, prompt, k + 1)
+    # margins of the continuation: the comparison below needs the GPU to agree with the oracle on these rows
+    o2 = OracleStepper(Decoder(shape, store, 96))
+    o2.prefill(prompt)
+    res = o2.verify(L0, cont[:k], route="rows")
+    assert res.accept_len == k and min(res.margins) >= 2 * TOL["bf16"], "pick another prompt: a near-tie on the greedy path"
+    g.prefill(prompt)
+    g.set_next(int(cont[0]))
+    hist = np.zeros(k + 1, dtype=np.int64)
+    for r in range(rounds):
+        draft = corrupt_drafts(11, r, cont[:k], p, shape.vocab)
+        changed = np.nonzero(np.asarray(draft) != np.asarray(cont[:k]))[0]
+        want = int(changed[0]) if changed.size else k
+        n, nxt = g.verify(L0, draft)
+        assert n == want, (r, n, want)
+        assert nxt == int(cont[n])          # the model's own token at the first mismatch / after a full window
+        hist[n] += 1
+    q = p * (1.0 - 1.0 / shape.vocab)
+    expect = np.array([(1 - q) ** j * q for j in range(k)] + [(1 - q) ** k]) * rounds
+    keep = expect >= 5                      # pool the sparse tail for the chi-square test
+    obs = np.append(hist[keep], hist[~keep].sum())
+    exp = np.append(expect[keep], expect[~keep].sum())
+    if exp[-1] == 0:
+        obs, exp = obs[:-1], exp[:-1]
+    assert chisquare(obs, exp).pvalue > 1e-4, (hist, expect)
+    g.free()
