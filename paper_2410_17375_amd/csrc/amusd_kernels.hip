@@ -741,7 +741,10 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
             const int p0 = (b0 + ib) * BK;
             if (p0 >= T) break;                         // wave-uniform: later blocks of the run hold no visible key
             uint4 kn[TPB][FR], vn[HT];
-            load_block(b0 + ib + 1, kn, vn);
+            // next block of the run; at the run's last useful block, fetch that block again (a cache hit)
+            // rather than a block the neighbouring run owns
+            const bool more = ib + 1 < bpw && p0 + BK < T;
+            load_block(more ? b0 + ib + 1 : b0 + ib, kn, vn);
             float sv[TPB][4];
             float mx = -INFINITY;
 #pragma unroll
