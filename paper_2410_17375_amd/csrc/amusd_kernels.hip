@@ -16,8 +16,8 @@
 //   * activations travel between stages as bf16 hi+lo pairs (x = hi + lo to
 //     ~16 mantissa bits), so the bf16 MFMA path loses nothing on the
 //     activation side; weights are exact bf16.
-// Every stage is a __device__ function over (workgroup id, workgroup count) so
-// the same code runs as one kernel per stage or inside one persistent kernel.
+// Every stage is a __device__ function over (workgroup id, workgroup count),
+// launched as one kernel per stage.
 #include <hip/hip_ext.h>
 #include <hip/hip_fp16.h>
 
