@@ -258,6 +258,8 @@ int amusd_stage_time(amusd_model *m, double *total_ms, int64_t *launches, int64_
  * values (which=1) of sequence 0 to host fp32 [n_kv_heads, n, head_dim], undoing the
  * library's internal layout.  Test hook. */
 int amusd_get_kv(amusd_model *m, int32_t layer, int32_t which, int32_t pos0, int32_t n, float *out);
+/* The same for sequence `seq`. */
+int amusd_seq_get_kv(amusd_model *m, int32_t seq, int32_t layer, int32_t which, int32_t pos0, int32_t n, float *out);
 
 /* Bytes of weights one pass streams from device memory, and bytes of cache it
  * reads at the given context and k (the algorithmic traffic used for roofline

@@ -88,6 +88,7 @@ def _load():
         "amusd_last_pass_ms": (C.c_int, [vp, f32p]),
         "amusd_stage_time": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]),
         "amusd_get_kv": (C.c_int, [vp, i32, i32, i32, i32, f32p]),
+        "amusd_seq_get_kv": (C.c_int, [vp, i32, i32, i32, i32, i32, f32p]),
         "amusd_weight_bytes_per_pass": (C.c_int64, [vp]),
         "amusd_kv_bytes_per_pass": (C.c_int64, [vp, i32, i32]),
         "amusd_calibration_copy": (C.c_int, [vp, vp, C.c_int64, vp]),
@@ -245,6 +246,11 @@ class Model:
     def get_kv(self, layer, which, pos0, n):
         out = np.empty((self.cfg.n_kv_heads, n, self.cfg.head_dim), dtype=np.float32)
         _check(lib.amusd_get_kv(self._h, layer, which, pos0, n, out.ctypes.data_as(C.POINTER(C.c_float))))
+        return out
+
+    def seq_get_kv(self, seq, layer, which, pos0, n):
+        out = np.empty((self.cfg.n_kv_heads, n, self.cfg.head_dim), dtype=np.float32)
+        _check(lib.amusd_seq_get_kv(self._h, seq, layer, which, pos0, n, out.ctypes.data_as(C.POINTER(C.c_float))))
         return out
 
     def weight_bytes_per_pass(self):

@@ -731,16 +731,20 @@ int amusd_stage_time(amusd_model* m, double* total_ms, int64_t* launches, int64_
 }
 
 int amusd_get_kv(amusd_model* m, int32_t layer, int32_t which, int32_t pos0, int32_t n, float* out) {
+    return amusd_seq_get_kv(m, 0, layer, which, pos0, n, out);
+}
+
+int amusd_seq_get_kv(amusd_model* m, int32_t seq, int32_t layer, int32_t which, int32_t pos0, int32_t n, float* out) {
     int rc = need_ready(m);
-    if (rc) return rc;
+    if (rc || (rc = need_seq(m, seq))) return rc;
     const DevModel& D = m->dm;
     if (!out || layer < 0 || layer >= D.n_layers || (which != 0 && which != 1) || pos0 < 0 || n < 1 || pos0 + n > D.ctx_pad)
         return fail(AMUSD_E_ARG, "get_kv: bad argument");
     const int esz = m->esz(), hd = D.hd, BK = m->block_keys(), EPL = 16 / esz;
     const size_t elems = (size_t)D.Hkv * D.ctx_pad * hd;
     std::vector<char> raw(elems * esz);
-    HIP_TRY(hipMemcpy(raw.data(), which ? m->layers_host[layer].vcache : m->layers_host[layer].kcache, raw.size(),
-                      hipMemcpyDeviceToHost));
+    const char* cache = reinterpret_cast<const char*>(which ? m->layers_host[layer].vcache : m->layers_host[layer].kcache);
+    HIP_TRY(hipMemcpy(raw.data(), cache + (size_t)seq * raw.size(), raw.size(), hipMemcpyDeviceToHost));
     auto val = [&](size_t i) {   // the cache of a 16-bit model holds IEEE half
         return esz == 2 ? half_bits_to_float(reinterpret_cast<const uint16_t*>(raw.data())[i])
                         : reinterpret_cast<const float*>(raw.data())[i];

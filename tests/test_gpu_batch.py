@@ -97,6 +97,14 @@ def test_batched_verify_matches_one_oracle_per_sequence(name):
                 assert g.seq_get_next(s) == res.next_token
             L[s] += res.accept_len
             row0 += k
+    # what the batched passes appended to each sequence's cache, against that sequence's oracle
+    for s in range(4):
+        n = min(g.seq_len(s), oracles[s].kv_len)
+        for l in range(shape.n_layers):
+            for which, ref in ((0, oracles[s].dec.K[l]), (1, oracles[s].dec.V[l])):
+                got = g.seq_get_kv(s, l, which, 0, n)
+                ktol = 1e-5 if shape.dtype == "fp32" else 2e-2
+                assert np.abs(got - ref[:, :n, :]).max() <= ktol, (s, l, which)
     print(f"{name}: worst batched logit error {worst:.3e}")
     g.free()
 
