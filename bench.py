@@ -84,7 +84,17 @@ def cpu_baseline(shape, L0, k, draft, target_seconds=20.0):
         del dec, store
     per_layer = (times[3] - times[1]) / 2.0
     full = times[1] + per_layer * (shape.n_layers - 1)
-    return {"value": full * 1e3, "unit": "ms", "cores": int(cores), "kind": "oracle",
+    cpu_model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return {"value": full * 1e3, "unit": "ms", "cores": int(cores), "host_cpus": os.cpu_count(), "cpu_model": cpu_model,
+            "kind": "oracle",
             "sample": f"oracle batched k={k} pass at ctx {L0}, float32, timed on the first 1 and 3 layers + LM head "
                       f"of the same weights (best of >=3), extrapolated linearly to {shape.n_layers} layers; "
                       f"cache filled with random values",
