@@ -209,7 +209,6 @@ int run_pass(amusd_model* m, const SegReq* segs, int n_seg, bool force_accept) {
     P.keep_logits = m->keep_logits ? 1 : 0;
     HIP_TRY(hipEventRecord(m->ev0, m->stream));
     HIP_TRY(launch_pass(m->dm, m->layers_host.data(), P, m->nwg, m->stream, m->timer.stage >= 0 ? &m->timer : nullptr));
-    HIP_TRY(hipMemcpyAsync(&h->res, m->dm.res, sizeof(PassResult), hipMemcpyDeviceToHost, m->stream));
     HIP_TRY(hipEventRecord(m->ev1, m->stream));
     HIP_TRY(hipStreamSynchronize(m->stream));
     HIP_TRY(hipEventElapsedTime(&m->last_ms, m->ev0, m->ev1));
@@ -369,7 +368,6 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
     ALLOC(D.logits, float*, kRows * V * 4, true)
     ALLOC(D.best_val, float*, (size_t)m->nwg * kRows * 4, true)
     ALLOC(D.best_idx, int*, (size_t)m->nwg * kRows * 4, true)
-    ALLOC(D.res, PassResult*, sizeof(PassResult), true)
 #undef ALLOC
     if (hipMemcpyAsync(const_cast<DevLayer*>(D.layers), m->layers_host.data(), sizeof(DevLayer) * c.n_layers,
                        hipMemcpyHostToDevice, m->stream) != hipSuccess)
@@ -377,6 +375,13 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
     if (hipHostMalloc(reinterpret_cast<void**>(&m->hstage), sizeof(HostStage), hipHostMallocDefault) != hipSuccess)
         return bail(fail(AMUSD_E_HIP, "pinned staging allocation"));
     std::memset(m->hstage, 0, sizeof(HostStage));
+    // the acceptance kernel writes its 192-byte result straight into this pinned host block: no copy per pass
+    {
+        void* dev = nullptr;
+        if (hipHostGetDevicePointer(&dev, m->hstage, 0) != hipSuccess)
+            return bail(fail(AMUSD_E_HIP, "device address of the pinned result block"));
+        D.res = reinterpret_cast<PassResult*>(dev);
+    }
     if (hipEventCreate(&m->ev0) != hipSuccess || hipEventCreate(&m->ev1) != hipSuccess)
         return bail(fail(AMUSD_E_HIP, "event creation"));
 
