@@ -119,6 +119,10 @@ def main():
                          "Table 1 (autoregressive, synchronous speculative, asynchronous) on one GPU: 8B-shape verify "
                          "model, 128-token prompt, 256 new tokens, with a random-weight 1B-shape draft model (nothing "
                          "it proposes is accepted) and with a copy of the verify model as draft (everything is)")
+    ap.add_argument("--calibrate-chain", action="store_true",
+                    help="run only chains of bare streaming kernels of the headline workload's stage sizes, each kernel "
+                         "depending on the one before: the time per kernel that any implementation of a stage as one "
+                         "kernel of a dependent chain has to beat (no arithmetic, no activations, no epilogue)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="run only a plain copy kernel of this size 10 times (profiler byte-counter calibration)")
     args = ap.parse_args()
@@ -144,6 +148,38 @@ def main():
             A.calibration_copy(dst.data_ptr(), src.data_ptr(), n)
         torch.cuda.synchronize()
         print(json.dumps({"calibration_copy_bytes_read": n, "calibration_copy_bytes_written": n, "launches": 10}))
+        return
+
+    if args.calibrate_chain:
+        sh = SHAPES["8b"]
+        e = sh.weight_elem_bytes
+        sizes = {"qkv": sh.d_model * (sh.q_dim + 2 * sh.kv_dim) * e, "oproj": sh.q_dim * sh.d_model * e,
+                 "gateup": 2 * sh.d_model * sh.d_ffn * e, "down": sh.d_model * sh.d_ffn * e,
+                 "lmhead": sh.vocab * sh.d_model * e}
+        buf = torch.ones(3 << 30, dtype=torch.uint8, device="cuda")
+        scratch = torch.zeros(3072, dtype=torch.uint8, device="cuda")
+        st = torch.cuda.Stream()
+        res = {}
+        with torch.cuda.stream(st):
+            for name, nbytes in sizes.items():
+                n = 40 if name == "lmhead" else 200
+                best = None
+                for _ in range(3):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(st)
+                    A.calibration_chain(buf.data_ptr(), buf.numel(), nbytes, n, scratch.data_ptr(), st.cuda_stream)
+                    e1.record(st)
+                    e1.synchronize()
+                    us = e0.elapsed_time(e1) * 1e3 / n
+                    best = us if best is None else min(best, us)
+                res[name] = {"bytes": int(nbytes), "us_per_kernel": round(best, 2),
+                             "gbps": round(nbytes / best / 1e3, 1)}
+        per_layer = sum(res[k]["us_per_kernel"] for k in ("qkv", "oproj", "gateup", "down"))
+        print(json.dumps({"bare_streaming_chain": res, "projection_stages_per_layer_us": round(per_layer, 2),
+                          "all_projection_stages_of_a_pass_ms": round((sh.n_layers * per_layer + res["lmhead"]["us_per_kernel"]) / 1e3, 4),
+                          "note": "256 workgroups x 512 threads, 16 non-temporal 16-byte loads in flight per thread, "
+                                  "kernels of one chain in one stream; attention, merge, embedding and acceptance "
+                                  "kernels (2 x 32 + 2 launches) are not included"}))
         return
 
     if args.loops:

@@ -273,6 +273,15 @@ int64_t amusd_kv_bytes_per_pass(const amusd_model *m, int32_t ctx_len, int32_t k
  * against which profiler byte counters are calibrated. */
 int amusd_calibration_copy(void *dst, const void *src, int64_t bytes, void *hip_stream);
 
+/* Enqueues n_kernels bare streaming kernels on the given HIP stream, each reading bytes_per_kernel bytes (a
+ * positive multiple of 2 MiB: 256 workgroups x 512 threads x 16 bytes) from `buf` (device memory of buf_bytes >=
+ * bytes_per_kernel; successive kernels take successive regions, wrapping around) with the load pattern of the
+ * projection stages and none of their arithmetic, and each depending on the one before.  scratch: 3 KiB of
+ * zeroed device memory.  Not part of the method: it measures what a chain of dependent kernels of a given size
+ * can reach on the machine, the yardstick the stage timings are held against.  The caller times the stream. */
+int amusd_calibration_chain(const void *buf, int64_t buf_bytes, int64_t bytes_per_kernel, int32_t n_kernels,
+                            void *scratch, void *hip_stream);
+
 /* Static description of a code; amusd_last_error gives the calling thread's
  * most recent detailed message (e.g. the HIP error string). */
 const char *amusd_strerror(int code);

@@ -6,9 +6,9 @@ names.  There is no CPU fallback: importing the binding without the built
 library raises.
 """
 from .binding import (AmusdError, Config, Model, LoopStats, generate_async, generate_sync,
-                      generate_greedy, calibration_copy, library_path, lib, TENSOR_IDS,
+                      generate_greedy, calibration_copy, calibration_chain, library_path, lib, TENSOR_IDS,
                       OPT_KEEP_LOGITS, OPT_TIME_STAGE, STAGES, DTYPE_FP32, DTYPE_BF16, MAX_K)
 
 __all__ = ["AmusdError", "Config", "Model", "LoopStats", "generate_async", "generate_sync",
-           "generate_greedy", "calibration_copy", "library_path", "lib", "TENSOR_IDS", "OPT_KEEP_LOGITS",
+           "generate_greedy", "calibration_copy", "calibration_chain", "library_path", "lib", "TENSOR_IDS", "OPT_KEEP_LOGITS",
            "OPT_TIME_STAGE", "STAGES", "DTYPE_FP32", "DTYPE_BF16", "MAX_K"]

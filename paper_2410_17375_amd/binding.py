@@ -92,6 +92,7 @@ def _load():
         "amusd_weight_bytes_per_pass": (C.c_int64, [vp]),
         "amusd_kv_bytes_per_pass": (C.c_int64, [vp, i32, i32]),
         "amusd_calibration_copy": (C.c_int, [vp, vp, C.c_int64, vp]),
+        "amusd_calibration_chain": (C.c_int, [vp, C.c_int64, C.c_int64, i32, vp, vp]),
         "amusd_strerror": (C.c_char_p, [C.c_int]),
         "amusd_last_error": (C.c_char_p, []),
     }
@@ -262,6 +263,11 @@ class Model:
 
 def calibration_copy(dst_ptr, src_ptr, nbytes, stream=0):
     _check(lib.amusd_calibration_copy(C.c_void_p(dst_ptr), C.c_void_p(src_ptr), nbytes, C.c_void_p(stream)))
+
+
+def calibration_chain(buf_ptr, buf_bytes, bytes_per_kernel, n_kernels, scratch_ptr, stream=0):
+    _check(lib.amusd_calibration_chain(C.c_void_p(buf_ptr), buf_bytes, bytes_per_kernel, n_kernels,
+                                       C.c_void_p(scratch_ptr), C.c_void_p(stream)))
 
 
 def _loop(fn, models, prompt, n_new, k_max):

@@ -796,6 +796,18 @@ int amusd_calibration_copy(void* dst, const void* src, int64_t bytes, void* hip_
     return AMUSD_OK;
 }
 
+int amusd_calibration_chain(const void* buf, int64_t buf_bytes, int64_t bytes_per_kernel, int32_t n_kernels, void* scratch,
+                            void* hip_stream) {
+    const int64_t unit = (int64_t)256 * kThreads * 16;       // one 16-byte load of every thread of every workgroup
+    if (!buf || !scratch || n_kernels < 1 || bytes_per_kernel < unit || bytes_per_kernel % unit ||
+        buf_bytes < bytes_per_kernel)
+        return fail(AMUSD_E_ARG, "calibration_chain: bytes_per_kernel must be a positive multiple of 2 MiB and fit the buffer");
+    float* io = reinterpret_cast<float*>(scratch);
+    HIP_TRY(launch_stream_chain(reinterpret_cast<const uint4*>(buf), (size_t)buf_bytes / 16, (size_t)bytes_per_kernel / 16,
+                                n_kernels, io, reinterpret_cast<unsigned*>(io + 512), reinterpret_cast<hipStream_t>(hip_stream)));
+    return AMUSD_OK;
+}
+
 // ---- drivers ------------------------------------------------------------------------------------
 
 namespace {

@@ -1055,6 +1055,52 @@ hipError_t launch_copy(uint4* dst, const uint4* src, size_t n, hipStream_t strea
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- bare streaming kernel (what a chain of dependent kernels can reach)
+// Reads `iters` x 8 KiB per workgroup (one contiguous run per workgroup, 16 non-temporal 16-byte loads in flight per
+// thread: the load pattern of the GEMM stages without their arithmetic), folds the data into one word per workgroup,
+// and chains on the previous launch through a 256-float vector it reads and rewrites.
+__global__ void __launch_bounds__(kThreads) k_stream_only(const uint4* __restrict__ src, int iters, const float* __restrict__ in,
+                                                          float* __restrict__ out, unsigned* __restrict__ fold) {
+    constexpr int PF = 16;
+    const int tid = threadIdx.x, wg = blockIdx.x;
+    const uint4* p = src + (size_t)wg * iters * kThreads + tid;
+    const int last = iters - 1;
+    uint4 buf[PF];
+#pragma unroll
+    for (int i = 0; i < PF; ++i) buf[i] = load_stream(p + (size_t)(i < last ? i : last) * kThreads);
+    const float a = in[(wg + 1) & 255];
+    unsigned acc = 0;
+    int s0 = 0;
+    for (; s0 + PF < iters; s0 += PF) {
+#pragma unroll
+        for (int i = 0; i < PF; ++i) {
+            acc += buf[i].x ^ buf[i].y ^ buf[i].z ^ buf[i].w;
+            const int sn = s0 + i + PF < last ? s0 + i + PF : last;
+            buf[i] = load_stream(p + (size_t)sn * kThreads);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < PF; ++i)
+        if (s0 + i < iters) acc += buf[i].x ^ buf[i].y ^ buf[i].z ^ buf[i].w;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if ((tid & 63) == 0) atomicAdd(&fold[wg & 255], acc);
+    if (tid == 0) out[wg & 255] = a + 1.0f;
+}
+
+hipError_t launch_stream_chain(const uint4* buf, size_t buf_words, size_t words_per_kernel, int n_kernels, float* io,
+                               unsigned* fold, hipStream_t stream) {
+    // words_per_kernel is a multiple of 256 workgroups x 512 threads; regions rotate through the buffer
+    const int iters = (int)(words_per_kernel / ((size_t)256 * kThreads));
+    const size_t regions = buf_words / words_per_kernel;
+    for (int i = 0; i < n_kernels; ++i) {
+        const uint4* src = buf + (size_t)(i % regions) * words_per_kernel;
+        hipLaunchKernelGGL(k_stream_only, dim3(256), dim3(kThreads), 0, stream, src, iters, io + 256 * (i & 1),
+                           io + 256 * ((i + 1) & 1), fold);
+    }
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- pass launch
 constexpr size_t kSmemBytes = (size_t)kSmemFloats * sizeof(float);
 
