@@ -165,6 +165,11 @@ __device__ __forceinline__ float wave_xor_add(float v, int off) { return v + __s
 // (so the fetch is the oldest entry of the load queue and never stalls the
 // weight stream) and reduced in a fixed order just before the epilogue.
 // Thread (row m = tid/32, slot s = tid%32) sums tiles s, s+32, ..; 512 threads.
+// LATE = true keeps the first use of the fetched values behind the contraction (an empty asm statement
+// stops the compiler from moving the loop-invariant sum in front of the round loop, where the wave would wait
+// for the values before it has asked for its first weights): 0.5 us per launch on the gate/up and LM-head
+// stages.  The QKV stage measured 0.2-1.3 us SLOWER that way and keeps the early use.
+template <bool LATE>
 struct RstdPrefetch {
     static constexpr int N = 8;      // covers d <= 4096 from registers; larger d loops in finish()
     float v[N];
@@ -175,7 +180,7 @@ struct RstdPrefetch {
         for (int t = 0; t < N; ++t) {
             const int idx = s + 32 * t;
             const float x = M.ssq[(idx < ntp ? idx : ntp - 1) * kRows + m];
-            v[t] = idx < ntp ? x : 0.f;
+            v[t] = LATE || idx < ntp ? x : 0.f;
         }
     }
     __device__ __forceinline__ void finish(const DevModel& M, float* rstd) {
@@ -183,7 +188,14 @@ struct RstdPrefetch {
         const int ntp = M.d / 16;
         float acc = 0.f;
 #pragma unroll
-        for (int t = 0; t < N; ++t) acc += v[t];
+        for (int t = 0; t < N; ++t) {
+            float x = v[t];
+            if constexpr (LATE) {
+                asm volatile("" : "+v"(x));
+                x = s + 32 * t < ntp ? x : 0.f;
+            }
+            acc += x;
+        }
         for (int idx = s + 32 * N; idx < ntp; idx += 32) acc += M.ssq[idx * kRows + m];
         acc = wave_xor_add(acc, 16);
         acc = wave_xor_add(acc, 8);
@@ -458,7 +470,7 @@ struct EpiQKV {
     float* rstd;         // LDS
     const PassArgs& P;
     int k_rows;
-    RstdPrefetch pre;
+    RstdPrefetch<false> pre;
     float pc[2], ps[2];
     __device__ __forceinline__ void prefetch(int t0, int stride, int nt) {
         const int hd = M.hd, tph = hd / 16, rot_tiles = (M.qdim + M.kvdim) / 16;
@@ -535,7 +547,7 @@ struct EpiSwiGLU {     // tile rows 0-7 are gate features, 8-15 the matching up 
     const DevModel& M;
     float* rstd;
     int k_rows;
-    RstdPrefetch pre;
+    RstdPrefetch<true> pre;
     __device__ __forceinline__ void prefetch(int, int, int) {}
     __device__ __forceinline__ void prepare() { pre.finish(M, rstd); }
     __device__ __forceinline__ void item(int tile, int /*slot*/, int /*it*/, int mm, int r, float v1, float v2, bool valid) {
@@ -567,7 +579,7 @@ struct EpiLMHead {
     int k_rows, keep;
     float run_v;         // thread mm < 16 keeps the workgroup's running best for row mm
     int run_i;
-    RstdPrefetch pre;
+    RstdPrefetch<true> pre;
     __device__ __forceinline__ void prefetch(int, int, int) {}
     __device__ __forceinline__ void prepare() { pre.finish(M, smem + kOffRstd); }
     __device__ __forceinline__ void item(int tile, int slot, int /*it*/, int mm, int r, float v1, float v2, bool valid) {
