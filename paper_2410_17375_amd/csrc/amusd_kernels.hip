@@ -254,6 +254,7 @@ __device__ __forceinline__ void gemm_accumulate(v4f (&out)[kMaxTilesPerRound], c
         for (int j = 0; j < NT; ++j) wb[i][j] = load_stream(wp[j] + (size_t)s * 64);
 #pragma unroll
         for (int f = 0; f < AF; ++f) ab[i][f] = ap[(size_t)s * (AF * 64) + f * 64];
+        __builtin_amdgcn_sched_barrier(0);   // same issue order as in the loop: the loop's waits are sized for it
     }
     int s0 = 0;
     for (; s0 + D < S; s0 += D) {
@@ -268,6 +269,10 @@ __device__ __forceinline__ void gemm_accumulate(v4f (&out)[kMaxTilesPerRound], c
             for (int j = 0; j < NT; ++j) wb[i][j] = load_stream(wp[j] + (size_t)sn * 64);
 #pragma unroll
             for (int f = 0; f < AF; ++f) ab[i][f] = ap[(size_t)sn * (AF * 64) + f * 64];
+            // Keep the stages in this order.  Left alone, the scheduler gathers the matrix instructions of all D
+            // stages first and all loads behind them, so a wave waits for its whole queue at the top of the loop
+            // and has nothing in flight while it computes.
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 #pragma unroll
