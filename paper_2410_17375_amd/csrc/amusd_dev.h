@@ -33,6 +33,13 @@ struct PassArgs {
     int n_seg;          // sequences in the pass
     int force_accept;   // 1: prefill, every row is kept
     int keep_logits;    // 1: store fp32 logits
+    // The first sequence's values once more, next to k: a pass of ONE sequence (the usual case) then needs nothing
+    // from the per-row and per-segment tables below, which a lane can only reach through dependent loads of the
+    // argument memory (a memory round trip each, before the kernel's first useful address is known).
+    int L0;             // seg[0].L
+    int slot0;          // seg[0].slot
+    int nchunks0;       // seg[0].nchunks
+    int units;          // attention work units of the pass, all sequences together
     int tokens[kRows];  // input token of each row
     int row_pos[kRows]; // position of each row in its sequence
     int row_seg[kRows]; // segment of each row

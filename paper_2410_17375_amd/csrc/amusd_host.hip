@@ -205,6 +205,10 @@ int run_pass(amusd_model* m, const SegReq* segs, int n_seg, bool force_accept) {
     }
     P.k = rows;
     P.n_seg = n_seg;
+    P.L0 = P.seg[0].L;
+    P.slot0 = P.seg[0].slot;
+    P.nchunks0 = P.seg[0].nchunks;
+    P.units = units;
     P.force_accept = force_accept ? 1 : 0;
     P.keep_logits = m->keep_logits ? 1 : 0;
     HIP_TRY(hipEventRecord(m->ev0, m->stream));

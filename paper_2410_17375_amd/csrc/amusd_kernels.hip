@@ -227,6 +227,9 @@ struct RstdPrefetch {
 // stages.  The order of a wave's additions depends on the workgroup and wave
 // only, never on k or on the position, so results stay independent of those.
 enum { kActSingle = 0, kActPacked8 = 1, kActHiLo = 2 };
+#ifndef AMUSD_QKV_LATE
+#define AMUSD_QKV_LATE false
+#endif
 #ifndef AMUSD_OLD_SHARE
 #define AMUSD_OLD_SHARE 8
 #endif
@@ -466,7 +469,9 @@ struct EpiResidual {   // O-projection and down-projection: X += C, feed the nex
     __device__ __forceinline__ void round_end(int) {}
 };
 
-template <class DT>
+// ONE: the pass holds one sequence, so a row's position and cache follow from three scalars next to k; otherwise
+// they are looked up per row in the argument tables (dependent loads of argument memory).
+template <class DT, bool ONE>
 struct EpiQKV {
     static constexpr int kStage = 1;        // RMS scale, rotary embedding on (i, i+hd/2) pairs, Q to its buffer, K/V appended to the cache
     static constexpr bool kStagger = false; // measured slower with staggered K walks (short slices, two tile counts)
@@ -475,8 +480,20 @@ struct EpiQKV {
     float* rstd;         // LDS
     const PassArgs& P;
     int k_rows;
-    RstdPrefetch<false> pre;
+    RstdPrefetch<AMUSD_QKV_LATE> pre;
     float pc[2], ps[2];
+    int pos, slot;       // of this thread's row (both items of a thread belong to the same row)
+    __device__ __forceinline__ void begin() {
+        const int mm = (threadIdx.x >> 3) & 15;
+        if constexpr (ONE) {
+            pos = P.L0 + mm;
+            slot = P.slot0;
+        } else {
+            pos = P.row_pos[mm];
+            slot = P.seg[P.row_seg[mm]].slot;
+        }
+        pre.begin(M);
+    }
     __device__ __forceinline__ void prefetch(int t0, int stride, int nt) {
         const int hd = M.hd, tph = hd / 16, rot_tiles = (M.qdim + M.kvdim) / 16;
 #pragma unroll
@@ -488,7 +505,6 @@ struct EpiQKV {
             const int tile = t0 + stride * j;
             if (j < nt && mm < k_rows && tile < rot_tiles) {
                 const int i = (tile % tph) * 8 + r;           // q and k sections both start at a head boundary
-                const int pos = P.row_pos[mm];
                 pc[it] = M.rope_cos[(size_t)pos * (hd / 2) + i];
                 ps[it] = M.rope_sin[(size_t)pos * (hd / 2) + i];
             }
@@ -500,8 +516,7 @@ struct EpiQKV {
         const int hd = M.hd, tph = hd / 16;
         const float sc = rstd[mm];
         const float x1 = v1 * sc, x2 = v2 * sc;
-        const int pos = P.row_pos[mm];
-        const size_t slot_base = (size_t)P.seg[P.row_seg[mm]].slot * M.Hkv * M.ctx_pad * hd;   // elements, K and V alike
+        const size_t slot_base = (size_t)slot * M.Hkv * M.ctx_pad * hd;   // elements, K and V alike
         const int qt = M.qdim / 16, kt = M.kvdim / 16;
         if (tile < qt + kt) {
             const bool isq = tile < qt;
@@ -651,11 +666,11 @@ __device__ __forceinline__ void stage_embed(const DevModel& M, const float* __re
     }
 }
 
-template <class DT>
+template <class DT, bool ONE>
 __device__ __forceinline__ void stage_qkv(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int nwg,
                                           float* smem) {
-    EpiQKV<DT> epi{M, Ly, smem + kOffRstd, P, P.k, {}, {}, {}};
-    epi.pre.begin(M);
+    EpiQKV<DT, ONE> epi{M, Ly, smem + kOffRstd, P, P.k, {}, {}, {}, 0, 0};
+    epi.begin();
     gemm_stage<DT>(Ly.wqkv, M.nqkv / 16, M.d / DT::KB, M.A, P.k, wg, nwg, epi, smem);
 }
 
@@ -707,7 +722,7 @@ __device__ __forceinline__ void stage_lmhead(const DevModel& M, const PassArgs& 
 // Output per (unit, head, row): numerator[hd], running max, denominator.
 constexpr int kPartRow = 4;   // floats appended to a partial's numerator: max, denominator, 2 pad (keeps 16-byte alignment)
 
-template <class DT, int HD>
+template <class DT, int HD, bool ONE>
 __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int nwg,
                                                 float* smem) {
     constexpr int FR = HD / 4 / DT::EPL;     // 16-byte fragments per lane along head_dim
@@ -715,7 +730,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
     constexpr int BK = DT::BLOCK_KEYS, TPB = DT::TPB;
     constexpr int HDP = HD + kAttPad;
     const int last = P.n_seg - 1;
-    const int units = P.seg[last].unit0 + M.Hkv * P.seg[last].nchunks;
+    const int units = P.units;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
     const int G = M.G, parts = kWaves / G, bpw = M.bpw;
@@ -726,13 +741,17 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
     const uint4 zero4 = uint4{0, 0, 0, 0};
     AMUSD_TP(2, wg, 0);
     for (int u = wg; u < units; u += nwg) {
-        int si = 0;
-        while (si < last && u >= P.seg[si + 1].unit0) ++si;
-        const PassSeg& S = P.seg[si];
-        const int L = S.L, k = S.k, row0 = S.row0, T = L + k, nchunks = S.nchunks;
-        const int ul = u - S.unit0;
+        int L = P.L0, k = P.k, row0 = 0, nchunks = P.nchunks0, cslot = P.slot0, unit0 = 0;
+        if constexpr (!ONE) {
+            int si = 0;
+            while (si < last && u >= P.seg[si + 1].unit0) ++si;
+            const PassSeg& S = P.seg[si];
+            L = S.L; k = S.k; row0 = S.row0; nchunks = S.nchunks; cslot = S.slot; unit0 = S.unit0;
+        }
+        const int T = L + k;
+        const int ul = u - unit0;
         const int kvh = ul / nchunks, c = ul % nchunks;
-        const size_t slot_frags = (size_t)S.slot * M.Hkv * M.ctx_pad * HD / DT::EPL;   // 16-byte fragments per cache
+        const size_t slot_frags = (size_t)cslot * M.Hkv * M.ctx_pad * HD / DT::EPL;   // 16-byte fragments per cache
         const bool mine = m >= row0 && m < row0 + k;     // tile row m belongs to this sequence
         const int head = kvh * G + hq;
         const int b0 = (c * parts + part) * bpw;       // first block of this wave's run
@@ -771,10 +790,19 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
             const int p0 = (b0 + ib) * BK;
             if (p0 >= T) break;                         // wave-uniform: later blocks of the run hold no visible key
             uint4 kn[TPB][FR], vn[HT];
-            // next block of the run; at the run's last useful block, fetch that block again (a cache hit)
-            // rather than a block the neighbouring run owns
+            // next block of the run, fetched while this one is used; nothing is fetched behind the run's last
+            // useful block (wave-uniform)
             const bool more = ib + 1 < bpw && p0 + BK < T;
-            load_block(more ? b0 + ib + 1 : b0 + ib, kn, vn);
+            if (more) {
+                load_block(b0 + ib + 1, kn, vn);
+            } else {
+#pragma unroll
+                for (int t = 0; t < TPB; ++t)
+#pragma unroll
+                    for (int i = 0; i < FR; ++i) kn[t][i] = zero4;
+#pragma unroll
+                for (int j = 0; j < HT; ++j) vn[j] = zero4;
+            }
             float sv[TPB][4];
             float mx = -INFINITY;
 #pragma unroll
@@ -831,6 +859,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
                 o[j] = DT::mfma_att(vf[j], ph, o[j]);
                 if constexpr (DT::HAS_LO) o[j] = DT::mfma_att(vf[j], pl, o[j]);
             }
+            if (!more) break;
 #pragma unroll
             for (int t = 0; t < TPB; ++t)
 #pragma unroll
@@ -879,7 +908,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
 // attention output as the O-projection's input.  One wave per (head, row):
 // lanes first hold one chunk each (max, weight, denominator), then one slice of
 // head_dim each.
-template <class DT, int HD>
+template <class DT, int HD, bool ONE>
 __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassArgs& P, int wg, int nwg) {
     const int k = P.k, CS = M.chunk;
     const int lane = threadIdx.x & 63;
@@ -890,9 +919,15 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassAr
     for (int x = gw; x < M.Hq * k; x += nw) {
         const int head = x / k, mm = x % k;
         const int kvh = head / M.G, hq = head % M.G;
-        const PassSeg& S = P.seg[P.row_seg[mm]];
-        const int nch = P.row_pos[mm] / CS + 1;       // chunks holding keys this row can see
-        const float* base = M.att_part + ((((size_t)S.unit0 + (size_t)kvh * S.nchunks) * M.G + hq) * kRows + mm) * ROW;
+        int unit0 = 0, nchunks = P.nchunks0, pos = P.L0 + mm;
+        if constexpr (!ONE) {
+            const PassSeg& S = P.seg[P.row_seg[mm]];
+            unit0 = S.unit0;
+            nchunks = S.nchunks;
+            pos = P.row_pos[mm];
+        }
+        const int nch = pos / CS + 1;                 // chunks holding keys this row can see
+        const float* base = M.att_part + ((((size_t)unit0 + (size_t)kvh * nchunks) * M.G + hq) * kRows + mm) * ROW;
         const size_t cstride = (size_t)M.G * kRows * ROW;
         float Mrun = -INFINITY, den = 0.f, num[PER];
 #pragma unroll
@@ -999,7 +1034,7 @@ __device__ __forceinline__ void stage_accept(const DevModel& M, const PassArgs& 
 
 // ---------------------------------------------------------------- one kernel per stage
 #define AMUSD_STAGE_KERNEL(name, body)                                                                     \
-    template <class DT, int HD>                                                                              \
+    template <class DT, int HD, bool ONE = false>                                                            \
     __global__ void __launch_bounds__(kThreads) name(DevModel M, DevLayer Ly, const float* gain, PassArgs P) { \
         extern __shared__ float smem[];                                                                      \
         (void)smem; (void)gain; (void)Ly;                                                                    \
@@ -1007,9 +1042,9 @@ __device__ __forceinline__ void stage_accept(const DevModel& M, const PassArgs& 
     }
 
 AMUSD_STAGE_KERNEL(k_embed, (stage_embed<DT>(M, gain, P, blockIdx.x, gridDim.x)))
-AMUSD_STAGE_KERNEL(k_qkv, (stage_qkv<DT>(M, Ly, P, blockIdx.x, gridDim.x, smem)))
-AMUSD_STAGE_KERNEL(k_attention, (stage_attention<DT, HD>(M, Ly, P, blockIdx.x, gridDim.x, smem)))
-AMUSD_STAGE_KERNEL(k_attn_merge, (stage_attn_merge<DT, HD>(M, P, blockIdx.x, gridDim.x)))
+AMUSD_STAGE_KERNEL(k_qkv, (stage_qkv<DT, ONE>(M, Ly, P, blockIdx.x, gridDim.x, smem)))
+AMUSD_STAGE_KERNEL(k_attention, (stage_attention<DT, HD, ONE>(M, Ly, P, blockIdx.x, gridDim.x, smem)))
+AMUSD_STAGE_KERNEL(k_attn_merge, (stage_attn_merge<DT, HD, ONE>(M, P, blockIdx.x, gridDim.x)))
 AMUSD_STAGE_KERNEL(k_oproj, (stage_oproj<DT>(M, Ly, P, blockIdx.x, gridDim.x, smem)))
 AMUSD_STAGE_KERNEL(k_gateup, (stage_gateup<DT>(M, Ly, P, blockIdx.x, gridDim.x, smem)))
 AMUSD_STAGE_KERNEL(k_down, (stage_down<DT>(M, Ly, gain, P, blockIdx.x, gridDim.x, smem)))
@@ -1130,6 +1165,13 @@ static hipError_t configure_one() {
     if (e != hipSuccess) return e;
     AMUSD_SET(k_qkv)
     AMUSD_SET(k_attention)
+#define AMUSD_SET_ONE(kern)                                                                                        \
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kern<DT, HD, true>),                                     \
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmemBytes);                           \
+    if (e != hipSuccess) return e;
+    AMUSD_SET_ONE(k_qkv)
+    AMUSD_SET_ONE(k_attention)
+#undef AMUSD_SET_ONE
     AMUSD_SET(k_oproj)
     AMUSD_SET(k_gateup)
     AMUSD_SET(k_down)
@@ -1161,7 +1203,7 @@ static hipError_t launch_pass_t(const DevModel& M, const DevLayer* Ls, const Pas
                                 StageTimer* tm) {
     const dim3 blk(kThreads);
     const int embed_wgs = (M.d / 16 + 3) / 4 < nwg ? (M.d / 16 + 3) / 4 : nwg;
-    const int att_units = P.seg[P.n_seg - 1].unit0 + M.Hkv * P.seg[P.n_seg - 1].nchunks;
+    const int att_units = P.units;
     const int att_wgs = att_units < nwg ? att_units : nwg;
     const int merge_wgs = M.Hq * P.k;      // one wave each
     const int qkv_wgs = M.nqkv / 16 < nwg ? M.nqkv / 16 : nwg;
@@ -1180,17 +1222,31 @@ static hipError_t launch_pass_t(const DevModel& M, const DevLayer* Ls, const Pas
         hipLaunchKernelGGL((kern<DT, HD>), dim3(grid), block, smem, s, M, Ls[layer], gain, P);                  \
     }
 #define AMUSD_LAUNCH(stage_id, kern, grid, smem, layer, gain) AMUSD_LAUNCH_T(stage_id, kern, grid, blk, smem, layer, gain)
+    // the stages that place rows in their sequences have a second form for a pass of one sequence
+#define AMUSD_LAUNCH_SEQ(stage_id, kern, grid, block, smem, layer)                                                \
+    if (P.n_seg == 1) {                                                                                           \
+        if (tm && tm->stage == stage_id) {                                                                        \
+            hipExtLaunchKernelGGL((kern<DT, HD, true>), dim3(grid), block, smem, s, tm->begin[tm->used],            \
+                                  tm->end[tm->used], 0, M, Ls[layer], nogain, P);                                 \
+            ++tm->used;                                                                                           \
+        } else {                                                                                                  \
+            hipLaunchKernelGGL((kern<DT, HD, true>), dim3(grid), block, smem, s, M, Ls[layer], nogain, P);          \
+        }                                                                                                         \
+    } else {                                                                                                      \
+        AMUSD_LAUNCH_T(stage_id, kern, grid, block, smem, layer, nogain)                                          \
+    }
     AMUSD_LAUNCH(0, k_embed, embed_wgs, 0, 0, Ls[0].g_attn)
     for (int l = 0; l < M.n_layers; ++l) {
         const float* gain_next = l + 1 < M.n_layers ? Ls[l + 1].g_attn : M.g_final;
-        AMUSD_LAUNCH(1, k_qkv, qkv_wgs, kSmemBytes, l, nogain)
-        AMUSD_LAUNCH(2, k_attention, att_wgs, kSmemBytes, l, nogain)
-        AMUSD_LAUNCH_T(3, k_attn_merge, merge_wgs, dim3(64), 0, l, nogain)
+        AMUSD_LAUNCH_SEQ(1, k_qkv, qkv_wgs, blk, kSmemBytes, l)
+        AMUSD_LAUNCH_SEQ(2, k_attention, att_wgs, blk, kSmemBytes, l)
+        AMUSD_LAUNCH_SEQ(3, k_attn_merge, merge_wgs, dim3(64), 0, l)
         AMUSD_LAUNCH(4, k_oproj, d_wgs, kSmemBytes, l, nogain)
         AMUSD_LAUNCH(5, k_gateup, gu_wgs, kSmemBytes, l, nogain)
         AMUSD_LAUNCH(6, k_down, d_wgs, kSmemBytes, l, gain_next)
     }
     AMUSD_LAUNCH(7, k_lmhead, M.lm_wgs, kSmemBytes, 0, nogain)
+#undef AMUSD_LAUNCH_SEQ
 #undef AMUSD_LAUNCH
 #undef AMUSD_LAUNCH_T
     if (tm && tm->stage == 8) {
