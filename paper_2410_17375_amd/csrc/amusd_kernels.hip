@@ -168,7 +168,7 @@ __device__ __forceinline__ float wave_xor_add(float v, int off) { return v + __s
 // LATE = true keeps the first use of the fetched values behind the contraction (an empty asm statement
 // stops the compiler from moving the loop-invariant sum in front of the round loop, where the wave would wait
 // for the values before it has asked for its first weights): 0.5 us per launch on the gate/up and LM-head
-// stages.  The QKV stage measured 0.2-1.3 us SLOWER that way and keeps the early use.
+// stages.  The QKV stage measured 0.2-2.8 us SLOWER that way and keeps the early use.
 template <bool LATE>
 struct RstdPrefetch {
     static constexpr int N = 8;      // covers d <= 4096 from registers; larger d loops in finish()
@@ -206,6 +206,16 @@ struct RstdPrefetch {
     }
 };
 
+// ---------------------------------------------------------------- LDS layout (dynamic shared memory, floats)
+constexpr int kAttPad = 4;    // row padding of the attention partials (spreads LDS banks)
+constexpr int kScratchFloats = kWaves * kRows * (128 + kAttPad) + kWaves * kRows * 2;   // attention partials; >= GEMM reduction area
+static_assert(kScratchFloats >= kWaves * kMaxTilesPerRound * 256, "GEMM reduction area must fit");
+constexpr int kOffRstd = kScratchFloats;
+constexpr int kOffTileBestV = kOffRstd + kRows;
+constexpr int kOffTileBestI = kOffTileBestV + kMaxTilesPerRound * kRows;
+constexpr int kOffPfSink = kOffTileBestI + kMaxTilesPerRound * kRows;   // per wave, 64 words nobody reads
+constexpr int kSmemFloats = kOffPfSink + kWaves * 64;
+
 // ---------------------------------------------------------------- skinny GEMM stage
 // C[n][m] = sum_k W[n][k] * A[m][k] for the 16 rows m, output tiles of 16
 // columns n.  Workgroup wg owns tiles wg, wg+nwg, ...; up to 8 per round.
@@ -227,9 +237,13 @@ struct RstdPrefetch {
 // stages.  The order of a wave's additions depends on the workgroup and wave
 // only, never on k or on the position, so results stay independent of those.
 enum { kActSingle = 0, kActPacked8 = 1, kActHiLo = 2 };
-#ifndef AMUSD_QKV_LATE
-#define AMUSD_QKV_LATE false
+#ifndef AMUSD_ATT_PF
+#define AMUSD_ATT_PF 12     // O-projection weight fragments (1 KiB) per wave fetched ahead by the attention stage
 #endif
+#ifndef AMUSD_ATT_PF_SLEEP
+#define AMUSD_ATT_PF_SLEEP 40   // s_sleep units (64 clocks) before the fetch: the attention units' own loads go first
+#endif
+
 #ifndef AMUSD_OLD_SHARE
 #define AMUSD_OLD_SHARE 8
 #endif
@@ -306,6 +320,60 @@ __device__ __forceinline__ void gemm_accumulate(v4f (&out)[kMaxTilesPerRound], c
     }
 }
 
+// A wave's share of the K blocks of a GEMM stage, and where in it the wave starts its walk.
+// K split: SIMD s hosts waves s and s+4; they share the K quarter of their SIMD.  The first wave of a
+// SIMD wins the issue arbitration and streams faster, so it takes the larger share (kOldShare/16).
+struct KSlice {
+    int kb0, S, rot;
+};
+__device__ __forceinline__ KSlice k_slice(int kblocks, int wg, int wave, bool stagger) {
+    const int simd = wave & 3, young = wave >> 2;
+    const int q0 = (kblocks * simd) / 4, q1 = (kblocks * (simd + 1)) / 4;
+    const int cut = q0 + ((q1 - q0) * kOldShare + 8) / 16;
+    KSlice k;
+    k.kb0 = young ? cut : q0;
+    k.S = (young ? q1 : cut) - k.kb0;
+    k.rot = stagger && k.S > 0 ? (int)(((unsigned)wg * 5u + (unsigned)wave * 11u) % (unsigned)k.S) : 0;
+    return k;
+}
+__device__ __forceinline__ int round_tiles(int left) { return left >= 8 ? 8 : left == 7 ? 7 : left >= 4 ? 4 : left >= 2 ? 2 : 1; }
+
+// Weights of a GEMM stage that runs later in the pass, fetched into L2 ahead of time.  The L2 of an XCD keeps what
+// its workgroups have read across kernel boundaries, and workgroup w of every stage runs on the same XCD
+// (w mod 8): reading one word of each 128-byte line of the fragments that workgroup wg of the later stage will
+// stream puts them where that workgroup will find them.  This only pays where the memory system would
+// otherwise sit idle (the attention stage waits on latency, not on bytes); between two streaming
+// stages it just moves bytes from one kernel to the other, and measured slower.  Weights are never written after
+// the model is loaded, so a line fetched early can never be stale.
+struct NextWeights {
+    const uint4* W;
+    int n_tiles, kblocks;
+    bool stagger;
+};
+// Fragments [F0, F1) of consumer wave `cwave`, counted in the order the consumer's pipeline asks for them
+// (stage-major over the tiles of its first round); 8 fragments (8 KiB) per load instruction of the calling wave.
+// The loads deliver straight into LDS (64 words per wave that nobody reads), so they need no result registers.
+template <int F0, int F1>
+__device__ __forceinline__ void prefetch_frags(const NextWeights& nx, int wg, int nwg, int cwave, int lane, float* lds_sink) {
+    if (F1 <= F0 || wg >= nx.n_tiles) return;
+    const KSlice ks = k_slice(nx.kblocks, wg, cwave, nx.stagger);
+    if (ks.S <= 0) return;
+    const int nt = round_tiles((nx.n_tiles - wg + nwg - 1) / nwg);
+#pragma unroll
+    for (int f0 = F0; f0 < F1; f0 += 8) {
+        const int f = f0 + (lane >> 3), q = lane & 7;
+        const int ff = f < F1 ? f : F1 - 1;                // lanes beyond the last fragment repeat it
+        const int i = ff / nt, j = ff % nt;
+        const int x = (i < ks.S ? i : ks.S - 1) + ks.rot;
+        const int blk = x >= ks.S ? x - ks.S : x;
+        const char* p = reinterpret_cast<const char*>(nx.W + ((size_t)(wg + nwg * j) * nx.kblocks + ks.kb0 + blk) * 64) + q * 128;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
+                                         (__attribute__((address_space(3))) void*)lds_sink, 4, 0, 0);
+    }
+}
+// A wave must not end while a load is in flight.
+__device__ __forceinline__ void prefetch_retire() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // MODE as above.  A wave hands one partial tile per output tile to the reduction, whatever the mode.
 template <class DT, int MODE, class Epi>
 __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_tiles, int kblocks,
@@ -313,21 +381,15 @@ __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_
     constexpr int SLOTS = kMaxTilesPerRound;                  // partial tiles per wave per round
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
-    // K split: SIMD s hosts waves s and s+4; they share the K quarter of their SIMD.  The first wave of a
-    // SIMD wins the issue arbitration and streams faster, so it takes the larger share (kOldShare/16).
-    const int simd = wave & 3, young = wave >> 2;
-    const int q0 = (kblocks * simd) / 4, q1 = (kblocks * (simd + 1)) / 4;
-    const int cut = q0 + ((q1 - q0) * kOldShare + 8) / 16;
-    const int kb0 = young ? cut : q0, kb1 = young ? q1 : cut;
-    const int S = kb1 - kb0;
-    const int rot = Epi::kStagger && S > 0 ? (int)(((unsigned)wg * 5u + (unsigned)wave * 11u) % (unsigned)S) : 0;
+    const KSlice ks = k_slice(kblocks, wg, wave, Epi::kStagger);
+    const int kb0 = ks.kb0, S = ks.S, rot = ks.rot;
     const int mine = wg < n_tiles ? (n_tiles - wg + nwg - 1) / nwg : 0;
     const uint4* act = reinterpret_cast<const uint4*>(A);
     bool first = true;
     AMUSD_TP(Epi::kStage, wg, 0);
     for (int i0 = 0; i0 < mine;) {
         const int left = mine - i0;
-        const int nt = left >= 8 ? 8 : left == 7 ? 7 : left >= 4 ? 4 : left >= 2 ? 2 : 1;
+        const int nt = round_tiles(left);
         const int t0 = wg + nwg * i0;
         epi.prefetch(t0, nwg, nt);
         if (first) AMUSD_TP(Epi::kStage, wg, 1);
@@ -480,20 +542,31 @@ struct EpiQKV {
     float* rstd;         // LDS
     const PassArgs& P;
     int k_rows;
-    RstdPrefetch<AMUSD_QKV_LATE> pre;
+    RstdPrefetch<false> pre;
     float pc[2], ps[2];
-    int pos, slot;       // of this thread's row (both items of a thread belong to the same row)
+    // Position and cache of this thread's row (both items of a thread belong to the same row).  The 16-bit form
+    // keeps them in two registers from the start of the kernel (0.5 us per launch faster than looking them up where
+    // they are used); the fp32 form's contraction loop has no register left for that and looks them up.
+    static constexpr bool kKeepRow = DT::HAS_LO;
+    int pos_, slot_;
+    __device__ __forceinline__ int lookup_pos(int mm) const {
+        if constexpr (ONE) return P.L0 + mm;
+        else return P.row_pos[mm];
+    }
+    __device__ __forceinline__ int lookup_slot(int mm) const {
+        if constexpr (ONE) return P.slot0;
+        else return P.seg[P.row_seg[mm]].slot;
+    }
     __device__ __forceinline__ void begin() {
-        const int mm = (threadIdx.x >> 3) & 15;
-        if constexpr (ONE) {
-            pos = P.L0 + mm;
-            slot = P.slot0;
-        } else {
-            pos = P.row_pos[mm];
-            slot = P.seg[P.row_seg[mm]].slot;
+        if constexpr (kKeepRow) {
+            const int mm = (threadIdx.x >> 3) & 15;
+            pos_ = lookup_pos(mm);
+            slot_ = lookup_slot(mm);
         }
         pre.begin(M);
     }
+    __device__ __forceinline__ int row_pos(int mm) const { return kKeepRow ? pos_ : lookup_pos(mm); }
+    __device__ __forceinline__ int row_slot(int mm) const { return kKeepRow ? slot_ : lookup_slot(mm); }
     __device__ __forceinline__ void prefetch(int t0, int stride, int nt) {
         const int hd = M.hd, tph = hd / 16, rot_tiles = (M.qdim + M.kvdim) / 16;
 #pragma unroll
@@ -505,6 +578,7 @@ struct EpiQKV {
             const int tile = t0 + stride * j;
             if (j < nt && mm < k_rows && tile < rot_tiles) {
                 const int i = (tile % tph) * 8 + r;           // q and k sections both start at a head boundary
+                const int pos = row_pos(mm);
                 pc[it] = M.rope_cos[(size_t)pos * (hd / 2) + i];
                 ps[it] = M.rope_sin[(size_t)pos * (hd / 2) + i];
             }
@@ -516,7 +590,8 @@ struct EpiQKV {
         const int hd = M.hd, tph = hd / 16;
         const float sc = rstd[mm];
         const float x1 = v1 * sc, x2 = v2 * sc;
-        const size_t slot_base = (size_t)slot * M.Hkv * M.ctx_pad * hd;   // elements, K and V alike
+        const int pos = row_pos(mm);
+        const size_t slot_base = (size_t)row_slot(mm) * M.Hkv * M.ctx_pad * hd;   // elements, K and V alike
         const int qt = M.qdim / 16, kt = M.kvdim / 16;
         if (tile < qt + kt) {
             const bool isq = tile < qt;
@@ -579,15 +654,6 @@ struct EpiSwiGLU {     // tile rows 0-7 are gate features, 8-15 the matching up 
     }
     __device__ __forceinline__ void round_end(int) {}
 };
-
-// ---------------------------------------------------------------- LDS layout (dynamic shared memory, floats)
-constexpr int kAttPad = 4;    // row padding of the attention partials (spreads LDS banks)
-constexpr int kScratchFloats = kWaves * kRows * (128 + kAttPad) + kWaves * kRows * 2;   // attention partials; >= GEMM reduction area
-static_assert(kScratchFloats >= kWaves * kMaxTilesPerRound * 256, "GEMM reduction area must fit");
-constexpr int kOffRstd = kScratchFloats;
-constexpr int kOffTileBestV = kOffRstd + kRows;
-constexpr int kOffTileBestI = kOffTileBestV + kMaxTilesPerRound * kRows;
-constexpr int kSmemFloats = kOffTileBestI + kMaxTilesPerRound * kRows;
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 
@@ -740,6 +806,21 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
     const int nblk = M.ctx_pad / BK;
     const uint4 zero4 = uint4{0, 0, 0, 0};
     AMUSD_TP(2, wg, 0);
+    // The O-projection's weights, fetched into L2 while this stage waits on latency, by the workgroups that have
+    // no attention unit (at short contexts there are fewer units than compute units).  Such a workgroup serves the
+    // O-projection workgroups of its own XCD in turn with the other idle workgroups of that XCD.
+    if (AMUSD_ATT_PF > 0 && wg >= units) {
+        const NextWeights wo{Ly.wo, M.d / 16, M.qdim / DT::KB, true};
+        const int consumers = wo.n_tiles < nwg ? wo.n_tiles : nwg;      // workgroups of the O-projection
+        const int x = wg & 7;
+        const int first = units + ((x - units) & 7);                    // first idle workgroup of XCD x
+        const int rank = (wg - first) >> 3, idle = (nwg - first + 7) >> 3;
+        if (AMUSD_ATT_PF_SLEEP > 0) __builtin_amdgcn_s_sleep(AMUSD_ATT_PF_SLEEP);   // the units' own loads go first
+        for (int t = rank; x + 8 * t < consumers; t += idle)
+            prefetch_frags<0, AMUSD_ATT_PF>(wo, x + 8 * t, consumers, wave, lane, smem + kOffPfSink + wave * 64);
+        prefetch_retire();
+        return;
+    }
     for (int u = wg; u < units; u += nwg) {
         int L = P.L0, k = P.k, row0 = 0, nchunks = P.nchunks0, cslot = P.slot0, unit0 = 0;
         if constexpr (!ONE) {
@@ -1204,7 +1285,7 @@ static hipError_t launch_pass_t(const DevModel& M, const DevLayer* Ls, const Pas
     const dim3 blk(kThreads);
     const int embed_wgs = (M.d / 16 + 3) / 4 < nwg ? (M.d / 16 + 3) / 4 : nwg;
     const int att_units = P.units;
-    const int att_wgs = att_units < nwg ? att_units : nwg;
+    const int att_wgs = AMUSD_ATT_PF > 0 ? nwg : att_units < nwg ? att_units : nwg;   // idle ones fetch ahead
     const int merge_wgs = M.Hq * P.k;      // one wave each
     const int qkv_wgs = M.nqkv / 16 < nwg ? M.nqkv / 16 : nwg;
     const int d_wgs = M.d / 16 < nwg ? M.d / 16 : nwg;
