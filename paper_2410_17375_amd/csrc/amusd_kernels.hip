@@ -228,7 +228,11 @@ constexpr int kSmemFloats = kOffPfSink + kWaves * 64;
 // unconditional (out-of-range stages re-read the last stage and multiply by a
 // zeroed activation), so the loop body is straight-line code and the hardware
 // load queue stays D stages deep: with 8 waves per CU that is 64-128 KiB of
-// weight bytes in flight per CU, what it takes to cover HBM latency.
+// weight bytes in flight per CU, what it takes to cover HBM latency.  Deeper is
+// not better: one- and two-tile rounds carry as many activation bytes as weight
+// bytes through the same queue, and measured fastest 8 KiB of weights deep per
+// wave (D = 8 and 4; 16 and 8 cost the down projection 1.1 us per launch, and a
+// bare streaming kernel is faster at 8 loads in flight per wave than at 16 or 24).
 //
 // A wave walks its K blocks from a start that depends on (workgroup, wave) and
 // wraps around (`rot`): 2048 waves that all begin at the first block of their
@@ -410,8 +414,8 @@ __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_
                     case 8: gemm_accumulate<DT, MODE, 8, 2>(acc, W, t0, nwg, kblocks, kb0, S, rot, act, lane); break;
                     case 7: gemm_accumulate<DT, MODE, 7, 2>(acc, W, t0, nwg, kblocks, kb0, S, rot, act, lane); break;
                     case 4: gemm_accumulate<DT, MODE, 4, 4>(acc, W, t0, nwg, kblocks, kb0, S, rot, act, lane); break;
-                    case 2: gemm_accumulate<DT, MODE, 2, 8>(acc, W, t0, nwg, kblocks, kb0, S, rot, act, lane); break;
-                    default: gemm_accumulate<DT, MODE, 1, 16>(acc, W, t0, nwg, kblocks, kb0, S, rot, act, lane); break;
+                    case 2: gemm_accumulate<DT, MODE, 2, 4>(acc, W, t0, nwg, kblocks, kb0, S, rot, act, lane); break;
+                    default: gemm_accumulate<DT, MODE, 1, 8>(acc, W, t0, nwg, kblocks, kb0, S, rot, act, lane); break;
                 }
             }
         }
