@@ -406,8 +406,8 @@ __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_
                     case 8: gemm_accumulate<DT, MODE, 8, 2>(acc, W, t0, nwg, kblocks, kb0, S, rot, act, lane); break;
                     case 7: gemm_accumulate<DT, MODE, 7, 2>(acc, W, t0, nwg, kblocks, kb0, S, rot, act, lane); break;
                     case 4: gemm_accumulate<DT, MODE, 4, 3>(acc, W, t0, nwg, kblocks, kb0, S, rot, act, lane); break;
-                    case 2: gemm_accumulate<DT, MODE, 2, 6>(acc, W, t0, nwg, kblocks, kb0, S, rot, act, lane); break;
-                    default: gemm_accumulate<DT, MODE, 1, 8>(acc, W, t0, nwg, kblocks, kb0, S, rot, act, lane); break;
+                    case 2: gemm_accumulate<DT, MODE, 2, 4>(acc, W, t0, nwg, kblocks, kb0, S, rot, act, lane); break;
+                    default: gemm_accumulate<DT, MODE, 1, 4>(acc, W, t0, nwg, kblocks, kb0, S, rot, act, lane); break;
                 }
             } else {
                 switch (nt) {
