@@ -244,6 +244,9 @@ enum { kActSingle = 0, kActPacked8 = 1, kActHiLo = 2 };
 #ifndef AMUSD_ATT_PF
 #define AMUSD_ATT_PF 12     // O-projection weight fragments (1 KiB) per wave fetched ahead by the attention stage
 #endif
+#ifndef AMUSD_ATT_PF_MAX
+#define AMUSD_ATT_PF_MAX 3      // O-projection workgroups served by one idle attention workgroup, at most
+#endif
 #ifndef AMUSD_ATT_PF_SLEEP
 #define AMUSD_ATT_PF_SLEEP 40   // s_sleep units (64 clocks) before the fetch: the attention units' own loads go first
 #endif
@@ -820,7 +823,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
         const int first = units + ((x - units) & 7);                    // first idle workgroup of XCD x
         const int rank = (wg - first) >> 3, idle = (nwg - first + 7) >> 3;
         if (AMUSD_ATT_PF_SLEEP > 0) __builtin_amdgcn_s_sleep(AMUSD_ATT_PF_SLEEP);   // the units' own loads go first
-        for (int t = rank; x + 8 * t < consumers; t += idle)
+        for (int t = rank, n = 0; x + 8 * t < consumers && n < AMUSD_ATT_PF_MAX; t += idle, ++n)
             prefetch_frags<0, AMUSD_ATT_PF>(wo, x + 8 * t, consumers, wave, lane, smem + kOffPfSink + wave * 64);
         prefetch_retire();
         return;
@@ -875,19 +878,11 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
             const int p0 = (b0 + ib) * BK;
             if (p0 >= T) break;                         // wave-uniform: later blocks of the run hold no visible key
             uint4 kn[TPB][FR], vn[HT];
-            // next block of the run, fetched while this one is used; nothing is fetched behind the run's last
-            // useful block (wave-uniform)
+            // next block of the run, fetched while this one is used; at the run's last useful block, that block
+            // again (a cache hit) rather than a block the neighbouring run owns: the fetch stays unconditional, so
+            // it is issued ahead of the matrix instructions, but nothing waits for the last one before the end
             const bool more = ib + 1 < bpw && p0 + BK < T;
-            if (more) {
-                load_block(b0 + ib + 1, kn, vn);
-            } else {
-#pragma unroll
-                for (int t = 0; t < TPB; ++t)
-#pragma unroll
-                    for (int i = 0; i < FR; ++i) kn[t][i] = zero4;
-#pragma unroll
-                for (int j = 0; j < HT; ++j) vn[j] = zero4;
-            }
+            load_block(more ? b0 + ib + 1 : b0 + ib, kn, vn);
             float sv[TPB][4];
             float mx = -INFINITY;
 #pragma unroll
@@ -944,7 +939,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
                 o[j] = DT::mfma_att(vf[j], ph, o[j]);
                 if constexpr (DT::HAS_LO) o[j] = DT::mfma_att(vf[j], pl, o[j]);
             }
-            if (!more) break;
+            if (!more) break;     // wave-uniform; the look-ahead fetch is retired at the end of the stage
 #pragma unroll
             for (int t = 0; t < TPB; ++t)
 #pragma unroll
@@ -987,6 +982,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
         __syncthreads();
         AMUSD_TP(2, wg, 5);
     }
+    prefetch_retire();
 }
 
 // Merge of the chunk partials of each (head, row) in chunk order -> normalised
