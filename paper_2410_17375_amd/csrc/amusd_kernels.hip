@@ -838,7 +838,19 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
         }
         const int T = L + k;
         const int ul = u - unit0;
-        const int kvh = ul / nchunks, c = ul % nchunks;
+        // Which (kv head, chunk) this unit is.  With a multiple of 8 kv heads, all chunks of a kv head go to
+        // workgroups of one XCD (workgroup index mod 8 = kv head mod 8), and so do the merge waves of its query
+        // heads: they then find the chunk partials in their own L2 instead of behind another XCD's write-back.
+        int kvh, c;
+        if ((M.Hkv & 7) == 0) {
+            const int b = ul >> 3;
+            kvh = (ul & 7) + 8 * (b / nchunks);
+            c = b % nchunks;
+        } else {
+            kvh = ul / nchunks;
+            c = ul % nchunks;
+        }
+        const int ucanon = unit0 + kvh * nchunks + c;      // where the merge stage looks for this unit's partials
         const size_t slot_frags = (size_t)cslot * M.Hkv * M.ctx_pad * HD / DT::EPL;   // 16-byte fragments per cache
         const bool mine = m >= row0 && m < row0 + k;     // tile row m belongs to this sequence
         const int head = kvh * G + hq;
@@ -974,7 +986,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
                 den += wt * partML[(sl * kRows + mm) * 2 + 1];
                 num += wt * *reinterpret_cast<const v4f*>(partO + ((size_t)(sl * kRows + mm) * HDP + c4 * 4));
             }
-            float* out = M.att_part + (((size_t)u * G + hh) * kRows + mm) * (HD + kPartRow);
+            float* out = M.att_part + (((size_t)ucanon * G + hh) * kRows + mm) * (HD + kPartRow);
             *reinterpret_cast<v4f*>(out + c4 * 4) = num;
             if (c4 == 0) { out[HD] = Mx; out[HD + 1] = den; }
         }
@@ -998,8 +1010,18 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassAr
     constexpr int PER = HD / 64, ROW = HD + kPartRow;
     AMUSD_TP(3, wg, 0);
     for (int x = gw; x < M.Hq * k; x += nw) {
-        const int head = x / k, mm = x % k;
-        const int kvh = head / M.G, hq = head % M.G;
+        int kvh, hq, mm;        // wave x -> (query head, row); same XCD as the attention units of the kv head
+        if ((M.Hkv & 7) == 0) {
+            const int y = x >> 3, per = M.G * k;
+            kvh = (x & 7) + 8 * (y / per);
+            hq = (y % per) / k;
+            mm = y % k;
+        } else {
+            kvh = (x / k) / M.G;
+            hq = (x / k) % M.G;
+            mm = x % k;
+        }
+        const int head = kvh * M.G + hq;
         int unit0 = 0, nchunks = P.nchunks0, pos = P.L0 + mm;
         if constexpr (!ONE) {
             const PassSeg& S = P.seg[P.row_seg[mm]];
