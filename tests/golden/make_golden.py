@@ -3,16 +3,31 @@
 
 Calls only the CPU oracle and the seeded workload generators; nothing here
 touches the HIP path.  For a workload (model shape, context length L0, window
-k) it runs the oracle over the context, takes the model's greedy continuation
-c[0..k] (c[0] is the model's token for position L0), and evaluates verify
-windows: the uncorrupted window c[0..k) and corrupted ones.  Per window it
-stores, for every row: the arg-max token, the top-2 margin, the eight largest
-logits with their ids, and the logits at fixed sampled vocabulary ids.
+k) it runs the oracle over the context, follows the model's greedy
+continuation c[0], c[1], ... (c[i] is the model's token for position L0+i),
+and evaluates verify windows.  A window sits at an offset o along that path:
+its context is the prompt followed by c[0..o), its drafts are c[o..o+k) or a
+corrupted copy.  Per window it stores accept_len, next_token and, for every
+row: the arg-max token, the top-2 margin, the eight largest logits with their
+ids, and the logits at fixed sampled vocabulary ids.
+
+A window can only pin the acceptance result when no row at or before its
+accept point is flagged (top-2 margin below the logit tolerance), so the
+script searches, deterministically:
+  * the smallest offset whose k greedy rows are all unflagged: the all-accept
+    window of the workload;
+  * corrupted windows at that offset, round after round of the seeded
+    corruption stream, until MIN_MISMATCH of them are unflagged up to their
+    accept point.
+The windows at offset 0 (uncorrupted and one per corruption rate) are stored
+whether flagged or not.  For the all-accept window, one logit of every
+16-column LM-head tile is stored as well (an .npz file beside the JSON).
 
 Arithmetic: float32 numpy (the 8B-shape model in float64 would need more host
-memory than the build machine has); weights are the bf16 values upcast.
+memory than the build machine has); weights are the bf16 values upcast and are
+generated once for all workloads given on the command line.
 
-    python tests/golden/make_golden.py 8b_k8_ctx2048 [--out tests/golden/8b_k8_ctx2048.json]
+    python tests/golden/make_golden.py 8b_k8_ctx2048 8b_k16_ctx16384
 """
 import argparse
 import hashlib
@@ -31,7 +46,7 @@ from oracle import Decoder, argmax_lowest, top2_margin          # noqa: E402
 from workload import SHAPES, WeightStore, prompt_tokens, corrupt_drafts   # noqa: E402
 
 WORKLOADS = {
-    # name: (shape, L0, k, seed, corruption probabilities of the extra windows)
+    # name: (shape, L0, k, seed, corruption probabilities of the windows at offset 0)
     "8b_k8_ctx2048": ("8b", 2048, 8, 2, (0.1, 0.3, 0.6)),
     "8b_k16_ctx16384": ("8b", 16384, 16, 3, (0.3,)),
     "1b_k5_ctx512": ("1b", 512, 5, 1, (0.3,)),
@@ -41,15 +56,43 @@ GREEDY = {
     "8b_greedy_p128_n256": ("8b", 128, 256, 4),
 }
 N_SAMPLED_IDS = 64
+TOL = 3e-2                 # logit tolerance of the 16-bit models: rows with a smaller top-2 margin are flagged
+MIN_MISMATCH = 3           # corrupted windows, unflagged up to the accept point, wanted per workload
+MAX_CORRUPT_ROUNDS = 24
+SEARCH_P = 0.3             # corruption rate of the searched windows
+SEARCH_ROUND0 = 2000       # first round index of the searched windows in the corruption stream
 
 
 def log(msg):
     print(f"[golden {time.strftime('%H:%M:%S')}] {msg}", flush=True)
 
 
+class KeptWeights:
+    """fp32 copies of a model's tensors, made once and shared by every decoder built here."""
+
+    def __init__(self, shape):
+        self._store = WeightStore(shape, cache=False)
+        self._kept = {}
+
+    def f32(self, name, layer=None):
+        key = (name, layer)
+        if key not in self._kept:
+            self._kept[key] = np.ascontiguousarray(self._store.f32(name, layer), dtype=np.float32)
+        return self._kept[key]
+
+    def bits(self, name, layer=None):
+        return self._store.bits(name, layer)
+
+
 def sampled_ids(vocab, seed):
     g = np.random.Generator(np.random.Philox(key=[seed, 77]))
     return np.sort(g.choice(vocab, size=N_SAMPLED_IDS, replace=False)).astype(np.int64)
+
+
+def tile_ids(vocab):
+    """One vocabulary id in every 16-column LM-head tile, the column varying from tile to tile."""
+    t = np.arange(vocab // 16, dtype=np.int64)
+    return t * 16 + (t * 7 + 3) % 16
 
 
 def describe_rows(logits, ids):
@@ -62,13 +105,12 @@ def describe_rows(logits, ids):
     return rows
 
 
-def greedy_sequence(name, out_path):
+def greedy_sequence(name, out_path, weights):
     """The verify model's plain greedy continuation of a prompt with the top-2
     margin at every position (the reference of the full decoding loops)."""
     shape_name, P, N, seed = GREEDY[name]
     shape = SHAPES[shape_name]
-    store = WeightStore(shape, cache=False)
-    dec = Decoder(shape, store, P + N + 1, dtype=np.float32, keep_weights=True)   # fp32 weights stay in memory
+    dec = Decoder(shape, weights, P + N + 1, dtype=np.float32, keep_weights=False)
     dec.progress = log
     prompt = prompt_tokens(seed, P, shape.vocab)
     z = dec.rows(prompt, logits_from=P - 1)
@@ -88,67 +130,135 @@ def greedy_sequence(name, out_path):
     log(f"wrote {out_path}")
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("workload", choices=sorted(WORKLOADS) + sorted(GREEDY))
-    ap.add_argument("--out")
-    ap.add_argument("--block", type=int, default=512, help="context rows per batched oracle pass")
-    args = ap.parse_args()
-    if args.workload in GREEDY:
-        greedy_sequence(args.workload, args.out or os.path.join(os.path.dirname(os.path.abspath(__file__)),
-                                                                args.workload + ".json"))
-        return
-    shape_name, L0, k, seed, ps = WORKLOADS[args.workload]
-    shape = SHAPES[shape_name]
-    out_path = args.out or os.path.join(os.path.dirname(os.path.abspath(__file__)), args.workload + ".json")
+def first_clean_run(margins, k, start=0):
+    """Smallest o >= start such that margins[o+1 .. o+k] (the rows of the window c[o..o+k)) are all >= TOL."""
+    for o in range(start, len(margins) - k):
+        if all(mg >= TOL for mg in margins[o + 1:o + k + 1]):
+            return o
+    return None
 
-    store = WeightStore(shape, cache=True)
-    dec = Decoder(shape, store, L0 + k + 1, dtype=np.float32, keep_weights=False)
+
+def verify_windows(name, out_dir, weights, block, max_extend):
+    shape_name, L0, k, seed, ps = WORKLOADS[name]
+    shape = SHAPES[shape_name]
+    out_path = os.path.join(out_dir, name + ".json")
+    dec = Decoder(shape, weights, L0 + max_extend + 2 * k + 2, dtype=np.float32, keep_weights=False)
     dec.progress = log
     prompt = prompt_tokens(seed, L0, shape.vocab)
-    log(f"{args.workload}: oracle over the {L0}-token context, {args.block} rows per pass")
+    log(f"{name}: oracle over the {L0}-token context, {block} rows per pass")
     last = None
-    for s in range(0, L0, args.block):
-        chunk = prompt[s:s + args.block]
+    for s in range(0, L0, block):
+        chunk = prompt[s:s + block]
         last = dec.rows(chunk, logits_from=len(chunk) - 1)
     dec.progress = None
     c = [argmax_lowest(last[-1])]
     margins_c = [top2_margin(last[-1])]
     log("greedy continuation, one token per step")
-    for j in range(k):
+    o_star = None
+    while True:
         z = dec.step(c[-1])
         c.append(argmax_lowest(z))
         margins_c.append(top2_margin(z))
-        log(f"  c[{j + 1}] = {c[-1]} (margin {margins_c[-1]:.4f})")
-    ids = sampled_ids(shape.vocab, seed)
-    windows = []
-    drafts = [("clean", np.array(c[:k], dtype=np.int64))]
-    for i, p in enumerate(ps):
-        drafts.append((f"p={p}", corrupt_drafts(seed, 1000 + i, c[:k], p, shape.vocab).astype(np.int64)))
-    for name, d in drafts:
-        dec.rollback(L0)
-        log(f"window {name}: {d.tolist()}")
+        n_c = len(c) - 1
+        if n_c % 8 == 0:
+            log(f"  {n_c} steps, last margin {margins_c[-1]:.4f}")
+        if n_c >= k:
+            o_star = first_clean_run(margins_c, k)
+            if o_star is not None or n_c >= max_extend + k:
+                break
+    log(f"continuation margins: {[round(x, 4) for x in margins_c]}")
+    log(f"all-accept offset: {o_star}")
+    # the greedy path's own cache rows: every window starts from them
+    end = dec.kv_len
+    snap = [(dec.K[l][:, L0:end, :].copy(), dec.V[l][:, L0:end, :].copy()) for l in range(dec.n_layers)]
+
+    def evaluate(wname, offset, d):
+        for l in range(dec.n_layers):
+            dec.K[l][:, L0:end, :] = snap[l][0]
+            dec.V[l][:, L0:end, :] = snap[l][1]
+        dec.kv_len = end
+        dec.rollback(L0 + offset)
         logits = dec.rows(d)
-        g = [argmax_lowest(z) for z in logits]
-        target = [c[0]] + g[:-1]
+        g = [argmax_lowest(zz) for zz in logits]
+        target = [c[offset]] + g[:-1]
         n = 0
         while n < k and d[n] == target[n]:
             n += 1
         nxt = target[n] if n < k else g[k - 1]
-        windows.append({"name": name, "draft": d.tolist(), "accept_len": n, "next_token": int(nxt),
-                        "rows": describe_rows(logits, ids)})
-    wq0 = store.bits("wq", 0)
+        rows = describe_rows(logits, ids)
+        flagged = [j for j, r in enumerate(rows) if r["margin"] < TOL]
+        assertable = not any(j <= min(n, k - 1) for j in flagged)
+        log(f"window {wname} @+{offset}: accept_len {n}, next {nxt}, flagged rows {flagged}, "
+            f"{'assertable' if assertable else 'flagged at or before the accept point'}")
+        return {"name": wname, "offset": offset, "draft": [int(t) for t in d], "accept_len": n, "next_token": int(nxt),
+                "assertable": assertable, "rows": rows}, logits
+
+    ids = sampled_ids(shape.vocab, seed)
+    windows = []
+    w, z0 = evaluate("clean", 0, np.array(c[:k], dtype=np.int64))
+    windows.append(w)
+    for i, p in enumerate(ps):
+        w, _ = evaluate(f"p={p}", 0, corrupt_drafts(seed, 1000 + i, c[:k], p, shape.vocab).astype(np.int64))
+        windows.append(w)
+    tile_doc = None
+    if o_star is not None:
+        full, zfull = windows[0], z0
+        while o_star is not None:
+            if o_star > 0:
+                full, zfull = evaluate(f"clean@{o_star}", o_star, np.array(c[o_star:o_star + k], dtype=np.int64))
+            if full["assertable"] and full["accept_len"] == k:
+                if o_star > 0:
+                    windows.append(full)
+                break
+            # the batched route's margins fell under the tolerance where the stepwise ones did not: next candidate
+            o_star = first_clean_run(margins_c, k, o_star + 1)
+        if o_star is not None:
+            tids = tile_ids(shape.vocab)
+            npz = name + ".tile_logits.npz"
+            np.savez_compressed(os.path.join(out_dir, npz), ids=tids, logits=zfull[:, tids].astype(np.float32))
+            tile_doc = {"file": npz, "window": full["name"]}
+            got, r = 0, 0
+            while got < MIN_MISMATCH and r < MAX_CORRUPT_ROUNDS:
+                d = corrupt_drafts(seed, SEARCH_ROUND0 + r, c[o_star:o_star + k], SEARCH_P, shape.vocab).astype(np.int64)
+                r += 1
+                if np.array_equal(d, c[o_star:o_star + k]):
+                    continue
+                w, _ = evaluate(f"p={SEARCH_P}@{o_star}#{SEARCH_ROUND0 + r - 1}", o_star, d)
+                if w["assertable"] and w["accept_len"] < k:
+                    windows.append(w)
+                    got += 1
+    wq0 = weights.bits("wq", 0)
     doc = {
-        "workload": args.workload, "shape": shape_name, "ctx": L0, "k": k, "seed": seed,
-        "oracle_dtype": "float32",
+        "workload": name, "shape": shape_name, "ctx": L0, "k": k, "seed": seed,
+        "oracle_dtype": "float32", "tol": TOL,
         "prompt_sha256": hashlib.sha256(prompt.tobytes()).hexdigest(),
         "wq0_sha256": hashlib.sha256(np.ascontiguousarray(wq0).tobytes()).hexdigest(),
         "continuation": [int(t) for t in c], "continuation_margins": margins_c,
+        "all_accept_offset": o_star, "tile_logits": tile_doc,
         "sampled_ids": ids.tolist(), "windows": windows,
     }
     with open(out_path, "w") as f:
         json.dump(doc, f, indent=1)
-    log(f"wrote {out_path}")
+    log(f"wrote {out_path}: {len(windows)} windows, {sum(w['assertable'] for w in windows)} assertable")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("workloads", nargs="+", choices=sorted(WORKLOADS) + sorted(GREEDY))
+    ap.add_argument("--out-dir", default=os.path.dirname(os.path.abspath(__file__)))
+    ap.add_argument("--block", type=int, default=512, help="context rows per batched oracle pass")
+    ap.add_argument("--max-extend", type=int, default=192,
+                    help="greedy steps beyond the context searched for an all-accept window")
+    args = ap.parse_args()
+    kept = {}
+    for name in args.workloads:
+        shape_name = (GREEDY.get(name) or WORKLOADS.get(name))[0]
+        if shape_name not in kept:
+            kept[shape_name] = KeptWeights(SHAPES[shape_name])
+        if name in GREEDY:
+            greedy_sequence(name, os.path.join(args.out_dir, name + ".json"), kept[shape_name])
+        else:
+            verify_windows(name, args.out_dir, kept[shape_name], args.block, args.max_extend)
 
 
 if __name__ == "__main__":
