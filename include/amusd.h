@@ -157,6 +157,23 @@ int amusd_prefill(amusd_model *m, const int32_t *tokens, int32_t n, int32_t *nex
 int amusd_verify(amusd_model *m, int32_t ctx_len, const int32_t *draft, int32_t k,
                  int32_t *accept_len, int32_t *next_token);
 
+/* amusd_verify for callers that cannot allocate device memory while they run (code under HIP graph capture
+ * around it, tight serving loops, harnesses that forbid allocation calls): the same pass with the same
+ * arguments, results and errors, bit for bit, but the buffers a pass keeps between its stages (residual stream,
+ * GEMM inputs, queries, attention partials, arg-max partials) live in one statically allocated device array of
+ * AMUSD_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the process ends, instead of in the
+ * model's own workspace.  The call makes no allocation of any kind (device, pinned or through another library).
+ * A model whose workspace does not fit (amusd_static_scratch_bytes above the limit: many sequences per pass,
+ * very wide models) is refused with AMUSD_E_CAPACITY and unchanged state.  All models on one GPU share the
+ * array and it keeps the last call's contents (the region is cleared when another model used it last), so two
+ * amusd_verify_static calls that overlap in time on one GPU race, also when they are for different models on
+ * different streams.  Inputs (weights, cache, drafts) and outputs are where amusd_verify has them. */
+#define AMUSD_STATIC_SCRATCH_BYTES (16 * 1024 * 1024)
+int amusd_verify_static(amusd_model *m, int32_t ctx_len, const int32_t *draft, int32_t k,
+                        int32_t *accept_len, int32_t *next_token);
+/* Bytes of the static array a pass of this model needs (a negative error code if m is NULL). */
+int64_t amusd_static_scratch_bytes(const amusd_model *m);
+
 /* GenerateToken (Algorithm 1, DraftProcess): feeds p_next at position kv_len,
  * appends its keys/values (kv_len grows by one) and returns the new p_next in
  * *token_out.  Same kernels as a pass with k = 1.  Errors: STATE, CAPACITY. */

@@ -67,6 +67,8 @@ def _load():
         "amusd_model_free": (C.c_int, [vp]),
         "amusd_prefill": (C.c_int, [vp, i32p, i32, i32p]),
         "amusd_verify": (C.c_int, [vp, i32, i32p, i32, i32p, i32p]),
+        "amusd_verify_static": (C.c_int, [vp, i32, i32p, i32, i32p, i32p]),
+        "amusd_static_scratch_bytes": (C.c_int64, [vp]),
         "amusd_draft_step": (C.c_int, [vp, i32p]),
         "amusd_kv_rollback": (C.c_int, [vp, i32]),
         "amusd_set_next": (C.c_int, [vp, i32]),
@@ -161,6 +163,15 @@ class Model:
         n, nxt = C.c_int32(-1), C.c_int32(-1)
         _check(lib.amusd_verify(self._h, ctx_len, p, a.size, C.byref(n), C.byref(nxt)))
         return n.value, nxt.value
+
+    def verify_static(self, ctx_len, draft):
+        a, p = _i32(draft)
+        n, nxt = C.c_int32(-1), C.c_int32(-1)
+        _check(lib.amusd_verify_static(self._h, ctx_len, p, a.size, C.byref(n), C.byref(nxt)))
+        return n.value, nxt.value
+
+    def static_scratch_bytes(self):
+        return int(lib.amusd_static_scratch_bytes(self._h))
 
     def draft_step(self):
         t = C.c_int32(-1)

@@ -42,6 +42,36 @@ struct HostStage {          // pinned: what one pass receives from the device
 
 }  // namespace
 
+// Workspace of the entry point that allocates nothing (amusd_verify_static): the buffers a pass keeps between its
+// stages (residual stream, GEMM inputs, queries, attention partials, arg-max partials) laid out in this one array
+// instead of the model's own allocations.  Every GPU the library runs on holds its own copy at its own address; in
+// host code the array's name is only a stand-in, so the address is asked for once per device, with that device
+// current, and kept.
+constexpr size_t kStaticScratchBytes = (size_t)AMUSD_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};          // device address of `scratch`, per device
+uint64_t g_scratch_owner[kMaxDevices] = {};     // model whose pass last laid out the array (0: none)
+uint64_t g_next_model_id = 1;
+
+// Device address of this device's copy of `scratch`; asked for on the first call per device.
+hipError_t static_scratch_address(int device, void** out) {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+}  // namespace
+
 struct SeqState {            // one sequence: its cache slot's length and the model's next token
     int kv_len = 0;
     int p_next = -1;
@@ -70,6 +100,9 @@ struct amusd_model {
     std::vector<void*> allocs;             // everything to hipFree
     std::vector<DevLayer> layers_host;
     DevModel dm{};
+    DevModel dm_static{};                  // dm with the pass workspace inside the static scratch array
+    size_t static_bytes = 0;               // bytes of the array that workspace takes
+    uint64_t id = 0;
     HostStage* hstage = nullptr;
     void* staging = nullptr;               // device staging for host-provided tensors
     size_t staging_bytes = 0;
@@ -178,8 +211,20 @@ hipError_t g_cfg_err = hipSuccess;
 
 // Runs one pass: segment i feeds segs[i].k tokens of sequence segs[i].seq at cache length segs[i].L.
 // Everything is already validated (distinct sequences, lengths, capacity, tokens, row total).
-int run_pass(amusd_model* m, const SegReq* segs, int n_seg, bool force_accept) {
+int run_pass(amusd_model* m, const SegReq* segs, int n_seg, bool force_accept, bool use_static = false) {
     HostStage* h = m->hstage;
+    if (use_static) {
+        // The array keeps what the last call on this GPU left in it.  A pass reads only what it has written itself
+        // in rows it owns, so nothing has to start at zero; the region is still cleared when another model used it
+        // last, so that the unused rows of the 16-row tiles never hold another model's values.  A fill kernel, not a
+        // memset: the call allocates nothing and stays usable where memset nodes are not.
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (g_scratch_owner[m->device] != m->id) {
+            HIP_TRY(launch_fill_zero(reinterpret_cast<uint4*>(g_scratch_ptr[m->device]), m->static_bytes / 16, m->stream));
+            g_scratch_owner[m->device] = m->id;
+        }
+    }
+    const DevModel& D = use_static ? m->dm_static : m->dm;
     PassArgs P;
     std::memset(&P, 0, sizeof(P));
     int rows = 0, units = 0;
@@ -212,7 +257,7 @@ int run_pass(amusd_model* m, const SegReq* segs, int n_seg, bool force_accept) {
     P.force_accept = force_accept ? 1 : 0;
     P.keep_logits = m->keep_logits ? 1 : 0;
     HIP_TRY(hipEventRecord(m->ev0, m->stream));
-    HIP_TRY(launch_pass(m->dm, m->layers_host.data(), P, m->nwg, m->stream, m->timer.stage >= 0 ? &m->timer : nullptr));
+    HIP_TRY(launch_pass(D, m->layers_host.data(), P, m->nwg, m->stream, m->timer.stage >= 0 ? &m->timer : nullptr));
     HIP_TRY(hipEventRecord(m->ev1, m->stream));
     HIP_TRY(hipStreamSynchronize(m->stream));
     HIP_TRY(hipEventElapsedTime(&m->last_ms, m->ev0, m->ev1));
@@ -366,7 +411,8 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
     ALLOC(D.Q_hi, void*, kRows * q * 4, true)
     ALLOC(D.Q_lo, void*, kRows * q * 4, true)
     const size_t pass_seqs = D.n_slots < kMaxSegs ? D.n_slots : kMaxSegs;
-    ALLOC(D.att_part, float*, pass_seqs * D.Hkv * D.max_chunks * D.G * kRows * (D.hd + 4) * 4, true)
+    const size_t att_part_bytes = pass_seqs * D.Hkv * D.max_chunks * D.G * kRows * (D.hd + 4) * 4;
+    ALLOC(D.att_part, float*, att_part_bytes, true)
     ALLOC(D.O, void*, kRows * q * 4, true)
     ALLOC(D.H, void*, kRows * F * 4, true)
     ALLOC(D.logits, float*, kRows * V * 4, true)
@@ -404,6 +450,35 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
         if (hipMemcpy(const_cast<float*>(D.rope_cos), cs.data(), cs.size() * 4, hipMemcpyHostToDevice) != hipSuccess ||
             hipMemcpy(const_cast<float*>(D.rope_sin), sn.data(), sn.size() * 4, hipMemcpyHostToDevice) != hipSuccess)
             return bail(fail(AMUSD_E_HIP, "rotary table upload"));
+    }
+    // The same workspace once more, inside the static scratch array (amusd_verify_static).
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        m->id = g_next_model_id++;
+    }
+    {
+        void* base = nullptr;
+        if (static_scratch_address(m->device, &base) != hipSuccess)
+            return bail(fail(AMUSD_E_HIP, "address of the static scratch array"));
+        m->dm_static = D;
+        size_t off = 0;
+        auto place = [&](size_t bytes) {
+            void* p = static_cast<char*>(base) + off;
+            off += (bytes + 255) & ~(size_t)255;
+            return p;
+        };
+        DevModel& S = m->dm_static;
+        S.X = static_cast<float*>(place(kRows * d * 4));
+        S.A = place(kRows * d * 4);
+        S.ssq = static_cast<float*>(place((d / 16) * kRows * 4));
+        S.Q_hi = place(kRows * q * 4);
+        S.Q_lo = place(kRows * q * 4);
+        S.att_part = static_cast<float*>(place(att_part_bytes));
+        S.O = place(kRows * q * 4);
+        S.H = place(kRows * F * 4);
+        S.best_val = static_cast<float*>(place((size_t)m->nwg * kRows * 4));
+        S.best_idx = static_cast<int*>(place((size_t)m->nwg * kRows * 4));
+        m->static_bytes = off;      // may exceed the array: amusd_verify_static then refuses the model
     }
     if (hipStreamSynchronize(m->stream) != hipSuccess) return bail(fail(AMUSD_E_HIP, "create: stream sync"));
     *out = m;
@@ -558,10 +633,15 @@ int amusd_prefill(amusd_model* m, const int32_t* tokens, int32_t n, int32_t* nex
     return amusd_seq_prefill(m, 0, tokens, n, next_token);
 }
 
-int amusd_verify_batch(amusd_model* m, int32_t n_seq, const int32_t* seq_ids, const int32_t* ctx_len, const int32_t* k,
-                       const int32_t* drafts, int32_t* accept_len, int32_t* next_token) {
+static int verify_batch_impl(amusd_model* m, int32_t n_seq, const int32_t* seq_ids, const int32_t* ctx_len,
+                             const int32_t* k, const int32_t* drafts, int32_t* accept_len, int32_t* next_token,
+                             bool use_static) {
     int rc = need_ready(m);
     if (rc) return rc;
+    if (use_static && m->static_bytes > kStaticScratchBytes)
+        return fail(AMUSD_E_CAPACITY, "verify_static: this model's pass workspace (" + std::to_string(m->static_bytes) +
+                                          " bytes) exceeds the static scratch array (" +
+                                          std::to_string(kStaticScratchBytes) + " bytes)");
     if (!seq_ids || !ctx_len || !k || !drafts || !accept_len || !next_token)
         return fail(AMUSD_E_ARG, "verify_batch: null argument");
     if (n_seq < 1 || n_seq > kMaxSegs) return fail(AMUSD_E_ARG, "verify_batch: n_seq outside [1, 16]");
@@ -583,12 +663,32 @@ int amusd_verify_batch(amusd_model* m, int32_t n_seq, const int32_t* seq_ids, co
     for (int i = 0; i < n_seq; ++i)
         if (m->seqs[seq_ids[i]].greedy_at[ctx_len[i]] < 0)
             return fail(AMUSD_E_STATE, "verify: the model's token for position ctx_len is unknown");
-    if ((rc = run_pass(m, segs, n_seq, false))) return rc;
+    if ((rc = run_pass(m, segs, n_seq, false, use_static))) return rc;
     for (int i = 0; i < n_seq; ++i) {
         accept_len[i] = m->hstage->res.accept_len[i];
         next_token[i] = m->hstage->res.next_token[i];
     }
     return AMUSD_OK;
+}
+
+int amusd_verify_batch(amusd_model* m, int32_t n_seq, const int32_t* seq_ids, const int32_t* ctx_len, const int32_t* k,
+                       const int32_t* drafts, int32_t* accept_len, int32_t* next_token) {
+    return verify_batch_impl(m, n_seq, seq_ids, ctx_len, k, drafts, accept_len, next_token, false);
+}
+
+int amusd_verify_static(amusd_model* m, int32_t ctx_len, const int32_t* draft, int32_t k, int32_t* accept_len,
+                        int32_t* next_token) {
+    int rc = need_ready(m);
+    if (rc) return rc;
+    if (!draft || !accept_len || !next_token) return fail(AMUSD_E_ARG, "verify_static: null argument");
+    if (k < 1 || k > m->cfg.max_k) return fail(AMUSD_E_ARG, "verify_static: k outside [1, max_k]");
+    const int32_t seq = 0;
+    return verify_batch_impl(m, 1, &seq, &ctx_len, &k, draft, accept_len, next_token, true);
+}
+
+int64_t amusd_static_scratch_bytes(const amusd_model* m) {
+    if (!m) return fail(AMUSD_E_ARG, "null model");
+    return (int64_t)m->static_bytes;
 }
 
 int amusd_verify(amusd_model* m, int32_t ctx_len, const int32_t* draft, int32_t k, int32_t* accept_len,

@@ -1210,6 +1210,19 @@ hipError_t launch_copy(uint4* dst, const uint4* src, size_t n, hipStream_t strea
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- zero fill (a kernel, so no memset node is needed)
+__global__ void __launch_bounds__(256) k_fill_zero(uint4* __restrict__ dst, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = uint4{0, 0, 0, 0};
+}
+
+hipError_t launch_fill_zero(uint4* dst, size_t n, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    const size_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)(blocks < 1024 ? blocks : 1024)), dim3(256), 0, stream, dst, n);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- bare streaming kernel (what a chain of dependent kernels can reach)
 // Reads `iters` x 8 KiB per workgroup (one contiguous run per workgroup, 16 non-temporal 16-byte loads in flight per
 // thread: the load pattern of the GEMM stages without their arithmetic), folds the data into one word per workgroup,

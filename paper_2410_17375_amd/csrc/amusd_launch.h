@@ -30,6 +30,9 @@ struct StageTimer {
 // Plain copy of n 16-byte words (profiler calibration).
 hipError_t launch_copy(uint4* dst, const uint4* src, size_t n, hipStream_t stream);
 
+// Writes n zeroed 16-byte words (a kernel: usable where a memset node is not).
+hipError_t launch_fill_zero(uint4* dst, size_t n, hipStream_t stream);
+
 // Enqueues n_kernels bare streaming kernels (256 workgroups, words_per_kernel 16-byte words each, regions of buf in
 // rotation), each depending on the one before.  io: 512 floats, fold: 256 words (device scratch of the caller).
 hipError_t launch_stream_chain(const uint4* buf, size_t buf_words, size_t words_per_kernel, int n_kernels, float* io,
