@@ -9,7 +9,8 @@
  *
  * Conventions
  *   - Every function returns AMUSD_OK (0) or a negative AMUSD_E_* code; it
- *     never throws or aborts.  On error the model's state is unchanged.
+ *     never throws or aborts.  On error the model's state is unchanged (amusd_prefill runs several passes:
+ *     if one fails, the cache length is restored to what it was before the call).
  *   - All pointers are owned by the caller.  The library copies what it needs:
  *     after a successful amusd_model_set_tensor / amusd_model_load the caller
  *     may free the weight buffers.  Output scalars/arrays are HOST memory and
@@ -43,7 +44,9 @@ extern "C" {
 #define AMUSD_E_NOMEM      -7   /* host allocation failure */
 
 #define AMUSD_DTYPE_FP32    0
-#define AMUSD_DTYPE_BF16    1
+#define AMUSD_DTYPE_BF16    1   /* weights bf16; the cache, queries and attention probabilities are kept as IEEE half
+                                  * (same 2 bytes, three more mantissa bits): keys, values and queries are assumed to
+                                  * lie within +-65504 and are clamped to that range when stored */
 
 #define AMUSD_MAX_K        16   /* rows of one pass: the 16-row matrix-core tile */
 #define AMUSD_MAX_SEQS   4096   /* sequences (key-value caches) one model can hold */
@@ -138,14 +141,16 @@ int amusd_model_free(amusd_model *m);
 
 /* ---- the steps of Algorithm 1 ------------------------------------------------------------- */
 
-/* "Initialize key-value caches with x": appends n tokens (host array) at
+/* Cache initialisation with the prompt (Algorithm 1, the state set-up before the two loops): appends n
+ * tokens (host array) at
  * positions kv_len .. kv_len+n-1 unconditionally, several rows per pass, and
  * returns in *next_token the greedy token after the last one.  next_token may
  * be NULL.  Errors: ARG, TOKEN, CAPACITY. */
 int amusd_prefill(amusd_model *m, const int32_t *tokens, int32_t n, int32_t *next_token);
 
 /* VerifyTokens + mismatch test + cache update (Algorithm 1, VerifyProcess).
- * First truncates the cache to ctx_len (must be in [1, kv_len]).  Row j feeds
+ * First truncates the cache to ctx_len (must be in [0, kv_len]; at ctx_len = 0 the model's token for
+ * position 0 is unknown unless amusd_set_next gave it, and the call fails with STATE).  Row j feeds
  * draft[j] (host array of k ids) at position ctx_len+j and attends to the
  * ctx_len cached positions plus rows 0..j.  With g[j] the arg-max token of row
  * j (lowest id on ties) and target = [p(ctx_len), g[0], .., g[k-2]], where
@@ -179,7 +184,8 @@ int64_t amusd_static_scratch_bytes(const amusd_model *m);
  * *token_out.  Same kernels as a pass with k = 1.  Errors: STATE, CAPACITY. */
 int amusd_draft_step(amusd_model *m, int32_t *token_out);
 
-/* "Roll back S to the state at p_v": sets kv_len = new_len in O(1), no data is
+/* Cache rollback (Algorithm 1, the draft side's reaction to the rollback flag; also how the verify cache
+ * drops rejected rows): sets kv_len = new_len in O(1), no data is
  * moved; p_next becomes the greedy token recorded for position new_len.
  * Errors: RANGE unless 0 <= new_len <= kv_len. */
 int amusd_kv_rollback(amusd_model *m, int32_t new_len);

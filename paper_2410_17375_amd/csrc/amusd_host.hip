@@ -621,9 +621,14 @@ int amusd_seq_prefill(amusd_model* m, int32_t seq, const int32_t* tokens, int32_
     if ((rc = check_tokens(m, tokens, n))) return rc;
     // 16-bit models run fastest with at most 8 rows per pass (hi and lo halves share one operand fragment)
     const int chunk = m->cfg.dtype == AMUSD_DTYPE_BF16 && m->cfg.max_k > 8 ? 8 : m->cfg.max_k;
+    const int len_before = q.kv_len, next_before = q.p_next;
     for (int s = 0; s < n; s += chunk) {
         const int k = n - s < chunk ? n - s : chunk;
-        if ((rc = run_pass(m, seq, q.kv_len, tokens + s, k, true))) return rc;
+        if ((rc = run_pass(m, seq, q.kv_len, tokens + s, k, true))) {
+            q.kv_len = len_before;          // the passes that succeeded are dropped again: an O(1) truncation
+            q.p_next = next_before;
+            return rc;
+        }
     }
     if (next_token) *next_token = q.p_next;
     return AMUSD_OK;

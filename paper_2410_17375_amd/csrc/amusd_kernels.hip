@@ -71,18 +71,6 @@ struct FP32 {
     static __device__ __forceinline__ float att_float(uint32_t b) { return __uint_as_float(b); }
 };
 
-#ifdef AMUSD_TRACE
-// Debug builds only: per-workgroup timestamps of the GEMM stages (wave 0).
-__device__ unsigned long long g_trace[8 * 256 * 8];
-__device__ unsigned long long g_trace_wave[8 * 256 * 8];   // [stage][wg][wave]: end of the wave's first contraction loop
-#define AMUSD_TP(stage, wg, idx)                                                                  \
-    do {                                                                                          \
-        if (threadIdx.x == 0 && (wg) < 256) g_trace[((stage) * 256 + (wg)) * 8 + (idx)] = wall_clock64(); \
-    } while (0)
-#else
-#define AMUSD_TP(stage, wg, idx) do { } while (0)
-#endif
-
 __device__ __forceinline__ uint32_t bf16_rne(float x) {
     uint32_t u = __float_as_uint(x);
     u += 0x7FFFu + ((u >> 16) & 1u);
@@ -241,20 +229,10 @@ constexpr int kSmemFloats = kOffPfSink + kWaves * 64;
 // stages.  The order of a wave's additions depends on the workgroup and wave
 // only, never on k or on the position, so results stay independent of those.
 enum { kActSingle = 0, kActPacked8 = 1, kActHiLo = 2 };
-#ifndef AMUSD_ATT_PF
-#define AMUSD_ATT_PF 12     // O-projection weight fragments (1 KiB) per wave fetched ahead by the attention stage
-#endif
-#ifndef AMUSD_ATT_PF_MAX
-#define AMUSD_ATT_PF_MAX 3      // O-projection workgroups served by one idle attention workgroup, at most
-#endif
-#ifndef AMUSD_ATT_PF_SLEEP
-#define AMUSD_ATT_PF_SLEEP 40   // s_sleep units (64 clocks) before the fetch: the attention units' own loads go first
-#endif
-
-#ifndef AMUSD_OLD_SHARE
-#define AMUSD_OLD_SHARE 8
-#endif
-constexpr int kOldShare = AMUSD_OLD_SHARE;   // sixteenths of a SIMD's K range given to its first wave
+constexpr int kAttPf = 12;        // O-projection weight fragments (1 KiB) per wave fetched ahead by the attention stage
+constexpr int kAttPfMax = 3;      // O-projection workgroups served by one idle attention workgroup, at most
+constexpr int kAttPfSleep = 40;   // s_sleep units (64 clocks) before the fetch: the attention units' own loads go first
+constexpr int kOldShare = 8;      // sixteenths of a SIMD's K range given to its first wave
 
 template <class DT, int MODE, int NT, int D>
 __device__ __forceinline__ void gemm_accumulate(v4f (&out)[kMaxTilesPerRound], const uint4* __restrict__ W, int tile0,
@@ -393,13 +371,11 @@ __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_
     const int mine = wg < n_tiles ? (n_tiles - wg + nwg - 1) / nwg : 0;
     const uint4* act = reinterpret_cast<const uint4*>(A);
     bool first = true;
-    AMUSD_TP(Epi::kStage, wg, 0);
     for (int i0 = 0; i0 < mine;) {
         const int left = mine - i0;
         const int nt = round_tiles(left);
         const int t0 = wg + nwg * i0;
         epi.prefetch(t0, nwg, nt);
-        if (first) AMUSD_TP(Epi::kStage, wg, 1);
         v4f acc[SLOTS];
 #pragma unroll
         for (int j = 0; j < SLOTS; ++j) acc[j] = v4f{0.f, 0.f, 0.f, 0.f};
@@ -428,13 +404,8 @@ __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_
         for (int j = 0; j < SLOTS; ++j)
             if (j < nt && (MODE != kActPacked8 || m < 8))
                 *reinterpret_cast<v4f*>(smem + ((wave * SLOTS + j) * 256 + m * 16 + g * 4)) = acc[j];
-        if (first) AMUSD_TP(Epi::kStage, wg, 2);
-#ifdef AMUSD_TRACE
-        if (first && lane == 0 && wg < 256) g_trace_wave[(Epi::kStage * 256 + wg) * 8 + wave] = wall_clock64();
-#endif
         if (first) epi.prepare();
         __syncthreads();
-        if (first) AMUSD_TP(Epi::kStage, wg, 3);
 #pragma unroll
         for (int it = 0; it * kThreads < SLOTS * 128; ++it) {
             const int item = tid + it * kThreads;
@@ -450,10 +421,8 @@ __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_
             }
             epi.item(t0 + nwg * (valid ? j : 0), j, it, mm, r, v1, v2, valid);
         }
-        if (first) AMUSD_TP(Epi::kStage, wg, 4);
         __syncthreads();
         epi.round_end(nt);
-        if (first) AMUSD_TP(Epi::kStage, wg, 5);
         first = false;
         i0 += nt;
     }
@@ -812,19 +781,18 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
     float* partML = smem + kWaves * kRows * HDP;       // [hq][part][16][2]
     const int nblk = M.ctx_pad / BK;
     const uint4 zero4 = uint4{0, 0, 0, 0};
-    AMUSD_TP(2, wg, 0);
     // The O-projection's weights, fetched into L2 while this stage waits on latency, by the workgroups that have
     // no attention unit (at short contexts there are fewer units than compute units).  Such a workgroup serves the
     // O-projection workgroups of its own XCD in turn with the other idle workgroups of that XCD.
-    if (AMUSD_ATT_PF > 0 && wg >= units) {
+    if (kAttPf > 0 && wg >= units) {
         const NextWeights wo{Ly.wo, M.d / 16, M.qdim / DT::KB, true};
         const int consumers = wo.n_tiles < nwg ? wo.n_tiles : nwg;      // workgroups of the O-projection
         const int x = wg & 7;
         const int first = units + ((x - units) & 7);                    // first idle workgroup of XCD x
         const int rank = (wg - first) >> 3, idle = (nwg - first + 7) >> 3;
-        if (AMUSD_ATT_PF_SLEEP > 0) __builtin_amdgcn_s_sleep(AMUSD_ATT_PF_SLEEP);   // the units' own loads go first
-        for (int t = rank, n = 0; x + 8 * t < consumers && n < AMUSD_ATT_PF_MAX; t += idle, ++n)
-            prefetch_frags<0, AMUSD_ATT_PF>(wo, x + 8 * t, consumers, wave, lane, smem + kOffPfSink + wave * 64);
+        if (kAttPfSleep > 0) __builtin_amdgcn_s_sleep(kAttPfSleep);   // the units' own loads go first
+        for (int t = rank, n = 0; x + 8 * t < consumers && n < kAttPfMax; t += idle, ++n)
+            prefetch_frags<0, kAttPf>(wo, x + 8 * t, consumers, wave, lane, smem + kOffPfSink + wave * 64);
         prefetch_retire();
         return;
     }
@@ -881,7 +849,6 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
             for (int j = 0; j < HT; ++j) vd[j] = vb[j * 64];
         };
         load_block(b0, kf, vf);
-        AMUSD_TP(2, wg, 1);
         float mrun = -INFINITY, lrun = 0.f;
         v4f o[HT];
 #pragma unroll
@@ -959,7 +926,6 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
 #pragma unroll
             for (int j = 0; j < HT; ++j) vf[j] = vn[j];
         }
-        AMUSD_TP(2, wg, 2);
         // run partial to LDS: o[j][e] is head_dim index 16j + 4g + e of row m
         const int slot = hq * parts + part;
 #pragma unroll
@@ -970,7 +936,6 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
             partML[(slot * kRows + m) * 2 + 1] = lrun;
         }
         __syncthreads();
-        AMUSD_TP(2, wg, 3);
         // merge the runs of each head in run order; item = (head, row, 4 consecutive head_dim entries)
         for (int x = tid; x < G * kRows * (HD / 4); x += kThreads) {
             const int c4 = x % (HD / 4), mm = (x / (HD / 4)) % kRows, hh = x / (kRows * (HD / 4));
@@ -990,9 +955,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
             *reinterpret_cast<v4f*>(out + c4 * 4) = num;
             if (c4 == 0) { out[HD] = Mx; out[HD + 1] = den; }
         }
-        AMUSD_TP(2, wg, 4);
         __syncthreads();
-        AMUSD_TP(2, wg, 5);
     }
     prefetch_retire();
 }
@@ -1008,7 +971,6 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassAr
     const int wpb = blockDim.x >> 6;
     const int gw = wg * wpb + (threadIdx.x >> 6), nw = nwg * wpb;
     constexpr int PER = HD / 64, ROW = HD + kPartRow;
-    AMUSD_TP(3, wg, 0);
     for (int x = gw; x < M.Hq * k; x += nw) {
         int kvh, hq, mm;        // wave x -> (query head, row); same XCD as the attention units of the kv head
         if ((M.Hkv & 7) == 0) {
@@ -1083,7 +1045,6 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassAr
 #pragma unroll
         for (int i = 0; i < PER; ++i)
             store_gemm_in<DT>(M.O, k, mm, head * HD + lane + 64 * i, num[i] * inv);
-        AMUSD_TP(3, wg, 5);
     }
 }
 
@@ -1296,14 +1257,6 @@ static hipError_t configure_one() {
     return hipSuccess;
 }
 
-#ifdef AMUSD_TRACE
-extern "C" int amusd_debug_read_trace(unsigned long long* out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_trace), sizeof(unsigned long long) * 8 * 256 * 8);
-}
-extern "C" int amusd_debug_read_trace_wave(unsigned long long* out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_trace_wave), sizeof(unsigned long long) * 8 * 256 * 8);
-}
-#endif
 
 hipError_t configure_kernels() {
     hipError_t e;
@@ -1320,7 +1273,7 @@ static hipError_t launch_pass_t(const DevModel& M, const DevLayer* Ls, const Pas
     const dim3 blk(kThreads);
     const int embed_wgs = (M.d / 16 + 3) / 4 < nwg ? (M.d / 16 + 3) / 4 : nwg;
     const int att_units = P.units;
-    const int att_wgs = AMUSD_ATT_PF > 0 ? nwg : att_units < nwg ? att_units : nwg;   // idle ones fetch ahead
+    const int att_wgs = kAttPf > 0 ? nwg : att_units < nwg ? att_units : nwg;   // idle ones fetch ahead
     const int merge_wgs = M.Hq * P.k;      // one wave each
     const int qkv_wgs = M.nqkv / 16 < nwg ? M.nqkv / 16 : nwg;
     const int d_wgs = M.d / 16 < nwg ? M.d / 16 : nwg;

@@ -84,7 +84,7 @@ inline int run_async(StepBackend& draft, StepBackend& verify, const int32_t* pro
             const int pd = p_d.load(std::memory_order_relaxed);
             if (pd < cap && draft.kv_len() < cap - 1 && draft.kv_len() == pd - 1) {
                 int32_t tok = -1;
-                const int e = draft.draft_step(&tok);      // GenerateToken(M_d, S_d): feeds D[pd-1], yields D[pd]
+                const int e = draft.draft_step(&tok);      // one draft-model step: feeds D[pd-1], yields D[pd]
                 if (e) { err.store(e); done.store(true, std::memory_order_release); break; }
                 ++steps;
                 D[pd] = tok;
@@ -94,7 +94,7 @@ inline int run_async(StepBackend& draft, StepBackend& verify, const int32_t* pro
                 std::this_thread::yield();
             }
             jit(2);
-            if (R.load(std::memory_order_acquire)) {       // roll S_d back to the state at p_v
+            if (R.load(std::memory_order_acquire)) {       // the verifier disagreed: truncate the draft cache to the corrected position
                 const int c = corr_pos;
                 int e = draft.rollback(c);
                 if (!e) e = draft.set_next(corr_tok);
@@ -108,7 +108,7 @@ inline int run_async(StepBackend& draft, StepBackend& verify, const int32_t* pro
         st.draft_steps = steps;
     });
 
-    // VerifyProcess on the calling thread
+    // the verify side runs on the calling thread
     while (!done.load(std::memory_order_acquire) && !expired()) {
         jit(4);
         const int L = p_v.load(std::memory_order_relaxed);
@@ -118,7 +118,7 @@ inline int run_async(StepBackend& draft, StepBackend& verify, const int32_t* pro
             if (k > k_max) k = k_max;
             if (k > cap - L) k = cap - L;
             int32_t n = 0, nxt = -1;
-            const int e = verify.verify(L, &D[L], k, &n, &nxt);   // T_v = VerifyTokens(M_v, S_v, D[p_v : p_d])
+            const int e = verify.verify(L, &D[L], k, &n, &nxt);   // one pass over the drafts published so far (at most k_max of them)
             if (e) { err.store(e); break; }
             for (int i = 0; i < n; ++i) V[L + i] = D[L + i];
             V[L + n] = nxt;
@@ -127,7 +127,7 @@ inline int run_async(StepBackend& draft, StepBackend& verify, const int32_t* pro
             ++st.accept_hist[n];
             jit(5);
             p_v.store(L + n, std::memory_order_release);
-            if (n < k) {                                          // mismatch: raise R
+            if (n < k) {                                          // a draft was wrong: publish the correction, then the flag
                 corr_pos = L + n;
                 corr_tok = nxt;
                 ++st.rollbacks;
@@ -137,10 +137,10 @@ inline int run_async(StepBackend& draft, StepBackend& verify, const int32_t* pro
             std::this_thread::yield();
         }
         const int pv = p_v.load(std::memory_order_relaxed);
-        if (pv + 1 - P >= n_new || pv + 1 >= cap) break;          // |V| >= N: signal completion
+        if (pv + 1 - P >= n_new || pv + 1 >= cap) break;          // token budget reached
         while (R.load(std::memory_order_acquire) && !done.load(std::memory_order_acquire) && !expired()) {
             jit(6);
-            std::this_thread::yield();                            // wait for the draft rollback
+            std::this_thread::yield();                            // until the draft side has truncated its cache
         }
     }
     done.store(true, std::memory_order_release);

@@ -58,7 +58,7 @@ def _force(g, s, full, L, p_next):
     g.seq_set_next(s, int(p_next))
 
 
-@pytest.mark.parametrize("name", ["tiny_verify", "tiny_gqa_fp32", "tiny_gqa_bf16", "tiny_gqa128_bf16"])
+@pytest.mark.parametrize("name", ["tiny_verify", "tiny_gqa_fp32", "tiny_gqa_bf16", "tiny_gqa128_bf16", "tiny_g8_bf16"])
 def test_batched_verify_matches_one_oracle_per_sequence(name):
     A, shape, g, oracles, fulls = _setup(name)
     tol, V = TOL[shape.dtype], shape.vocab

@@ -55,7 +55,8 @@ def _check_rows(shape, g, logits_ref, k, where):
     return err, flagged
 
 
-@pytest.mark.parametrize("name", ["tiny_verify", "tiny_draft", "tiny_gqa_fp32", "tiny_gqa_bf16", "tiny_gqa128_bf16"])
+@pytest.mark.parametrize("name", ["tiny_verify", "tiny_draft", "tiny_gqa_fp32", "tiny_gqa_bf16", "tiny_gqa128_bf16",
+                                  "tiny_g8_bf16"])
 def test_prefill_and_verify_rounds_match_oracle(name):
     shape, g, o = _pair(name, 320)
     V = shape.vocab
@@ -64,18 +65,21 @@ def test_prefill_and_verify_rounds_match_oracle(name):
     pos, worst = 0, 0.0
     for n in (16, 1, 7, 16, 13, 11):
         piece = prompt[pos:pos + n]
-        nxt = g.prefill(piece)
         ref = o.dec.rows(piece)
         for j in range(n):
             o.greedy_at[pos + j + 1] = int(np.argmax(ref[j]))
-        # 16-bit models prefill at most 8 rows per pass; the logits kept are those of the last pass
-        last = n if shape.dtype == "fp32" else (n - 1) % 8 + 1
-        err, flagged = _check_rows(shape, g, ref[n - last:], last, f"{name} prefill@{pos}")
-        worst = max(worst, err)
+        # 16-bit models prefill at most 8 rows per pass and keep the logits of the last pass only: feed them
+        # pass by pass, so that every pass's logits are compared
+        step = n if shape.dtype == "fp32" else 8
+        for s0 in range(0, n, step):
+            sub = piece[s0:s0 + step]
+            nxt = g.prefill(sub)
+            err, flagged = _check_rows(shape, g, ref[s0:s0 + len(sub)], len(sub), f"{name} prefill@{pos + s0}")
+            worst = max(worst, err)
+            assert g.kv_len() == pos + s0 + len(sub)
+            if len(sub) - 1 not in flagged:
+                assert nxt == int(np.argmax(ref[s0 + len(sub) - 1]))
         pos += n
-        assert g.kv_len() == pos
-        if last - 1 not in flagged:
-            assert nxt == int(np.argmax(ref[-1]))
     assert pos == 64
     o.p_next = int(o.greedy_at[64])
     # cache contents
@@ -108,7 +112,42 @@ def test_prefill_and_verify_rounds_match_oracle(name):
     print(f"{name}: worst logit error {worst:.3e}")
 
 
-@pytest.mark.parametrize("name", ["tiny_verify", "tiny_gqa_bf16", "tiny_gqa128_bf16"])
+def test_long_cache_of_one_kv_head_reaches_every_merge_path():
+    """One kv head, context 4800: 76 attention chunks of 64 keys, so the merge of chunk partials runs its
+    second group of 64 chunks and the path beyond the partials it prefetches; passes of 8 rows and of 16 rows
+    (the 16-bit model's two operand forms) against the float64 oracle, element by element."""
+    A, load_model = _gpu()
+    from oracle import Decoder, OracleStepper
+    shape = SHAPES["tiny_gqa128_bf16"]
+    L0 = 4800
+    store = WeightStore(shape)
+    g = load_model(shape, L0 + 64, store=store)
+    g.set_option(A.OPT_KEEP_LOGITS, 1)
+    o = OracleStepper(Decoder(shape, store, L0 + 64))
+    prompt = prompt_tokens(31, L0 + 40, shape.vocab)
+    o.prefill(prompt[:L0])
+    g.prefill(prompt[:L0])
+    for l in range(shape.n_layers):
+        for which, ref in ((0, o.dec.K[l]), (1, o.dec.V[l])):
+            assert np.abs(g.get_kv(l, which, 0, L0) - ref[:, :L0, :]).max() <= 2e-2, (l, which)
+    worst = 0.0
+    for L, k in ((L0, 8), (L0 + 8, 16), (L0 + 24, 1), (L0 + 25, 11)):
+        piece = prompt[L:L + k]
+        ref = o.dec.rows(piece)
+        assert g.kv_len() == L
+        if k <= 8:
+            g.prefill(piece)                         # one pass of k rows
+        else:
+            g.verify(L, piece)                       # one pass of k rows (16-bit models prefill 8 rows at a time)
+        err, _ = _check_rows(shape, g, ref, k, f"long cache @{L} k={k}")
+        worst = max(worst, err)
+        if g.kv_len() < L + k:                       # the verify call kept only the accepted rows: feed the rest
+            g.prefill(prompt[g.kv_len():L + k])
+    print(f"long cache: worst logit error {worst:.3e}")
+    g.free()
+
+
+@pytest.mark.parametrize("name", ["tiny_verify", "tiny_gqa_bf16", "tiny_gqa128_bf16", "tiny_g8_bf16"])
 def test_k_row_pass_equals_k_single_row_passes_bitwise(name):
     """On the GPU itself a row's result must not depend on how many rows the pass has."""
     A, load_model = _gpu()

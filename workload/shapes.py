@@ -57,6 +57,8 @@ SHAPES = {
     # tiny bf16 GQA model: exercises grouped heads, head_dim 128 and bf16 storage at CPU-test size
     "tiny_gqa_bf16": ModelShape("tiny_gqa_bf16", 2, 256, 4, 2, 64, 512, 2048, "bf16", 500000.0, seed=7),
     "tiny_gqa128_bf16": ModelShape("tiny_gqa128_bf16", 2, 512, 4, 1, 128, 1024, 2048, "bf16", 500000.0, seed=8),
+    # one kv head shared by eight query heads (the largest group the attention stage supports), bf16
+    "tiny_g8_bf16": ModelShape("tiny_g8_bf16", 2, 256, 8, 1, 64, 512, 2048, "bf16", 500000.0, seed=10),
     "tiny_gqa_fp32": ModelShape("tiny_gqa_fp32", 2, 256, 8, 2, 32 * 2, 512, 2048, "fp32", 500000.0, seed=9),
     # 1B shape (draft model shape; also a verify workload of its own)
     "1b": ModelShape("1b", 16, 2048, 32, 8, 64, 8192, 32000, "bf16", 500000.0, seed=1),
