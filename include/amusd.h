@@ -19,6 +19,11 @@
  *     is enqueued there.  Calls on one model must not overlap; calls on
  *     different models may run concurrently from different host threads.
  *   - Token ids are int32 in [0, vocab).  Positions count tokens from 0.
+ *   - A pass is a chain of ~6 short dependent kernels per layer, each of which starts by reading its arguments.
+ *     The quoted latencies hold with the HIP runtime keeping kernel arguments in device memory
+ *     (HIP_FORCE_DEV_KERNARG=1 in the environment before the process's first HIP call; the Python binding sets
+ *     it when imported first); with arguments in host memory every kernel waits for PCIe and an 8B-shape pass
+ *     takes about 12 % longer.  The library itself cannot change this setting.
  *
  * Per-sequence state: kv_len (tokens in the sequence's cache) and p_next, the
  * model's greedy token for position kv_len (known once the cache is non-empty).

@@ -231,7 +231,8 @@ constexpr int kSmemFloats = kOffPfSink + kWaves * 64;
 enum { kActSingle = 0, kActPacked8 = 1, kActHiLo = 2 };
 constexpr int kAttPf = 12;        // O-projection weight fragments (1 KiB) per wave fetched ahead by the attention stage
 constexpr int kAttPfMax = 3;      // O-projection workgroups served by one idle attention workgroup, at most
-constexpr int kAttPfSleep = 40;   // s_sleep units (64 clocks) before the fetch: the attention units' own loads go first
+constexpr int kAttPfSleep = 0;    // s_sleep units (64 clocks) before the fetch (0: at once; the units find their cache rows in L2)
+constexpr bool kKvPrefetch = true; // QKV workgroups with time to spare fetch the cache rows the attention stage reads next
 constexpr int kOldShare = 8;      // sixteenths of a SIMD's K range given to its first wave
 
 template <class DT, int MODE, int NT, int D>
@@ -714,6 +715,38 @@ __device__ __forceinline__ void stage_qkv(const DevModel& M, const DevLayer& Ly,
     EpiQKV<DT, ONE> epi{M, Ly, smem + kOffRstd, P, P.k, {}, {}, {}, 0, 0};
     epi.begin();
     gemm_stage<DT>(Ly.wqkv, M.nqkv / 16, M.d / DT::KB, M.A, P.k, wg, nwg, epi, smem);
+    // The workgroups that own one tile fewer than the others finish early.  They use the time to fetch the layer's
+    // cached keys and values into L2 for the attention stage, which is next and waits on exactly those loads:
+    // the attention units of kv head h run on XCD h mod 8, and so does every workgroup with that index mod 8.
+    // Only whole key blocks below the first position this pass writes are touched (one word per 128-byte line,
+    // delivered to LDS words nobody reads), so no line is fetched that this kernel may still change.
+    if constexpr (ONE) {
+        const int n_tiles = M.nqkv / 16;
+        const int rounds = (n_tiles + nwg - 1) / nwg;
+        const int w0 = n_tiles - (rounds - 1) * nwg;              // first workgroup with one tile fewer
+        if (kKvPrefetch && (M.Hkv & 7) == 0 && rounds > 1 && w0 < nwg && wg >= w0) {
+            const int x = wg & 7;
+            const int first = w0 + ((x - w0) & 7);                    // first such workgroup of XCD x
+            const int rank = (wg - first) >> 3, count = (nwg - first + 7) >> 3;
+            const int safe = P.L0 / DT::BLOCK_KEYS * DT::BLOCK_KEYS;  // positions in blocks this pass leaves alone
+            const int half = (int)((size_t)safe * M.hd * DT::ESZ / 128);   // lines of one head's keys (values alike)
+            const int total = (M.Hkv >> 3) * 2 * half;                // lines for this XCD's kv heads
+            const int share = (total + count - 1) / count;
+            const size_t head_bytes = (size_t)M.ctx_pad * M.hd * DT::ESZ;
+            const size_t slot_bytes = (size_t)P.slot0 * M.Hkv * head_bytes;
+            const int end = (rank + 1) * share < total ? (rank + 1) * share : total;
+            for (int line = rank * share + (int)threadIdx.x; line < end; line += kThreads) {
+                const int hi = line / (2 * half), within = line % (2 * half);
+                const char* base = reinterpret_cast<const char*>(within < half ? Ly.kcache : Ly.vcache);
+                const char* p = base + slot_bytes + (size_t)(x + 8 * hi) * head_bytes +
+                                (size_t)(within < half ? within : within - half) * 128;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
+                                                 (__attribute__((address_space(3))) void*)(smem + kOffPfSink + (threadIdx.x >> 6) * 64),
+                                                 4, 0, 0);
+            }
+            prefetch_retire();
+        }
+    }
 }
 
 template <class DT>
