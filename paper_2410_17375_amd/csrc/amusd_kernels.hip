@@ -146,6 +146,12 @@ __device__ __forceinline__ uint4 load_frag(const void* base, size_t elem_index) 
     return *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(base) + elem_index * DT::ESZ);
 }
 
+// Forces a (wave-uniform) kernel argument into a scalar register at this point of the program.  Left to itself
+// the compiler loads an argument where it is first used, often behind a branch; a stage that starts by asking
+// for everything it needs waits for argument memory once instead of several times in a row.
+template <class T>
+__device__ __forceinline__ void pin_scalar(const T& x) { asm volatile("" ::"s"(x)); }
+
 __device__ __forceinline__ float wave_xor_add(float v, int off) { return v + __shfl_xor(v, off, 64); }
 
 // ---------------------------------------------------------------- RMS scale of the 16 rows
@@ -800,6 +806,10 @@ constexpr int kPartRow = 4;   // floats appended to a partial's numerator: max, 
 template <class DT, int HD, bool ONE>
 __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int nwg,
                                                 float* smem) {
+    pin_scalar(M.Q_hi); pin_scalar(M.Q_lo); pin_scalar(Ly.kcache); pin_scalar(Ly.vcache); pin_scalar(M.att_part);
+    pin_scalar(Ly.wo); pin_scalar(M.d); pin_scalar(M.qdim); pin_scalar(M.Hkv); pin_scalar(M.ctx_pad);
+    pin_scalar(M.att_scale); pin_scalar(M.G); pin_scalar(M.bpw); pin_scalar(P.L0); pin_scalar(P.k);
+    pin_scalar(P.nchunks0); pin_scalar(P.slot0); pin_scalar(P.units); pin_scalar(P.n_seg);
     constexpr int FR = HD / 4 / DT::EPL;     // 16-byte fragments per lane along head_dim
     constexpr int HT = HD / 16;              // 16-wide head_dim tiles
     constexpr int BK = DT::BLOCK_KEYS, TPB = DT::TPB;
@@ -999,6 +1009,8 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
 // head_dim each.
 template <class DT, int HD, bool ONE>
 __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassArgs& P, int wg, int nwg) {
+    pin_scalar(M.att_part); pin_scalar(M.O); pin_scalar(M.Hq); pin_scalar(M.Hkv); pin_scalar(M.G); pin_scalar(M.chunk);
+    pin_scalar(P.k); pin_scalar(P.L0); pin_scalar(P.nchunks0);
     const int k = P.k, CS = M.chunk;
     const int lane = threadIdx.x & 63;
     const int wpb = blockDim.x >> 6;
