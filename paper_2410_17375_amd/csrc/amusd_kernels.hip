@@ -238,6 +238,7 @@ enum { kActSingle = 0, kActPacked8 = 1, kActHiLo = 2 };
 constexpr int kAttPf = 12;        // O-projection weight fragments (1 KiB) per wave fetched ahead by the attention stage
 constexpr int kAttPfMax = 3;      // O-projection workgroups served by one idle attention workgroup, at most
 constexpr int kAttPfSleep = 0;    // s_sleep units (64 clocks) before the fetch (0: at once; the units find their cache rows in L2)
+constexpr size_t kKvPrefetchMax = 2u << 20;   // cache bytes per XCD up to which they do (context 4096 at the 8B shape)
 constexpr bool kKvPrefetch = true; // QKV workgroups with time to spare fetch the cache rows the attention stage reads next
 constexpr int kOldShare = 8;      // sixteenths of a SIMD's K range given to its first wave
 
@@ -730,7 +731,10 @@ __device__ __forceinline__ void stage_qkv(const DevModel& M, const DevLayer& Ly,
         const int n_tiles = M.nqkv / 16;
         const int rounds = (n_tiles + nwg - 1) / nwg;
         const int w0 = n_tiles - (rounds - 1) * nwg;              // first workgroup with one tile fewer
-        if (kKvPrefetch && (M.Hkv & 7) == 0 && rounds > 1 && w0 < nwg && wg >= w0) {
+        // as long as those rows are a small part of an XCD's L2 (they are read once; the O-projection's weights,
+        // fetched by the attention stage, need the rest of it)
+        const size_t per_xcd = (size_t)(M.Hkv >> 3) * 2 * P.L0 * M.hd * DT::ESZ;
+        if (kKvPrefetch && (M.Hkv & 7) == 0 && rounds > 1 && w0 < nwg && wg >= w0 && per_xcd <= kKvPrefetchMax) {
             const int x = wg & 7;
             const int first = w0 + ((x - w0) & 7);                    // first such workgroup of XCD x
             const int rank = (wg - first) >> 3, count = (nwg - first + 7) >> 3;
