@@ -73,6 +73,7 @@ struct DevModel {
     int bpw;              // key blocks a wave walks in one attention work unit
     int max_chunks;
     int lm_wgs;           // workgroups that produce arg-max partials
+    int split_down;       // 1: the down projection's tiles are shared by two workgroups each (K halves)
     float eps, att_scale;
     const DevLayer* layers;
     const void* embed;    // [V][d] storage dtype, row-major
@@ -86,6 +87,8 @@ struct DevModel {
     void* Q_hi;           // [16][qdim]
     void* Q_lo;
     float* att_part;      // [units][G][16][hd+4]: numerator[hd], max, denominator, 2 pad; units <= n_slots*Hkv*max_chunks
+    float* xch;           // [d/16 tiles][2 K halves][16 rows][16 columns]: partial tiles of a stage split over workgroup pairs
+    int* xch_ticket;      // [d/16]: halves of the tile finished so far
     void* O;              // merged attention output, operand order, qdim columns
     void* H;              // SwiGLU output, operand order, F columns
     float* logits;        // [16][V]

@@ -448,6 +448,89 @@ __device__ __forceinline__ void gemm_stage(const uint4* __restrict__ W, int n_ti
     }
 }
 
+// ---------------------------------------------------------------- K split over a pair of workgroups
+// Words that one workgroup writes and a workgroup on another compute unit reads inside the same kernel: every
+// access is a relaxed atomic at device scope, which the hardware carries out past the caches that are private to
+// a compute unit or to one of the chip's eight dies.
+__device__ __forceinline__ void store_shared_f(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_shared_f(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// A stage with at most half as many tiles as there are compute units and a long contraction (the down projection
+// of a narrow model) leaves half the chip without work, and what a compute unit can pull through its load path
+// then bounds the stage.  Here two workgroups share a tile: workgroup `tile` contracts over the lower half of the
+// K blocks, workgroup `n_tiles + tile` over the upper half.  Each writes its partial tile to device memory and
+// counts itself; whichever counts second adds the other's partial to its own (a + b, the same bits whoever is
+// second) and runs the epilogue.  Nobody waits for anybody.  kblocks is even (the host checks).
+template <class DT, int MODE, class Epi>
+__device__ __forceinline__ void gemm_stage_split_m(const uint4* __restrict__ W, int n_tiles, int kblocks,
+                                                   const void* __restrict__ A, int wg, Epi& epi, float* smem,
+                                                   float* xch, int* ticket) {
+    constexpr int SLOTS = kMaxTilesPerRound;
+    constexpr int D = MODE == kActHiLo ? 4 : 8;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 15, g = lane >> 4;
+    const int tile = wg % n_tiles, half = wg / n_tiles;
+    const int kh = kblocks / 2;
+    const KSlice ks = k_slice(kh, wg, wave, Epi::kStagger);
+    const uint4* act = reinterpret_cast<const uint4*>(A);
+    epi.prefetch(tile, 0, 1);
+    v4f acc[SLOTS];
+#pragma unroll
+    for (int j = 0; j < SLOTS; ++j) acc[j] = v4f{0.f, 0.f, 0.f, 0.f};
+    if (ks.S > 0) gemm_accumulate<DT, MODE, 1, D>(acc, W, tile, 0, kblocks, ks.kb0 + half * kh, ks.S, ks.rot, act, lane);
+    if (MODE != kActPacked8 || m < 8) *reinterpret_cast<v4f*>(smem + (wave * SLOTS * 256 + m * 16 + g * 4)) = acc[0];
+    epi.prepare();
+    __syncthreads();
+    const int mm = (tid >> 3) & 15, r = tid & 7;
+    const bool valid = tid < 128 && (MODE != kActPacked8 || mm < 8);
+    float v1 = 0.f, v2 = 0.f;
+    if (valid) {
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            v1 += smem[w * SLOTS * 256 + mm * 16 + r];
+            v2 += smem[w * SLOTS * 256 + mm * 16 + r + 8];
+        }
+        float* mine = xch + ((size_t)tile * 2 + half) * 256;
+        store_shared_f(mine + mm * 16 + r, v1);
+        store_shared_f(mine + mm * 16 + r + 8, v2);
+    }
+    // the partial is complete in device memory once every wave's stores have been acknowledged; then it is counted
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    int* s_flag = reinterpret_cast<int*>(smem + kOffTileBestI);
+    if (tid == 0) {
+        const int seen = __hip_atomic_fetch_add(ticket + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (seen == 1) __hip_atomic_store(ticket + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next layer
+        *s_flag = seen == 1;
+    }
+    __syncthreads();
+    if (!*s_flag) return;                     // the other workgroup of the pair finishes the tile
+    if (valid) {
+        const float* other = xch + ((size_t)tile * 2 + (1 - half)) * 256;
+        v1 += load_shared_f(other + mm * 16 + r);
+        v2 += load_shared_f(other + mm * 16 + r + 8);
+    }
+    epi.item(tile, 0, 0, mm, r, v1, v2, valid);
+    __syncthreads();
+    epi.round_end(1);
+}
+
+template <class DT, class Epi>
+__device__ __forceinline__ void gemm_stage_split(const uint4* __restrict__ W, int n_tiles, int kblocks,
+                                                 const void* __restrict__ A, int k_rows, int wg, Epi& epi, float* smem,
+                                                 float* xch, int* ticket) {
+    if constexpr (!DT::HAS_LO) {
+        gemm_stage_split_m<DT, kActSingle>(W, n_tiles, kblocks, A, wg, epi, smem, xch, ticket);
+    } else {
+        if (k_rows <= 8) gemm_stage_split_m<DT, kActPacked8>(W, n_tiles, kblocks, A, wg, epi, smem, xch, ticket);
+        else gemm_stage_split_m<DT, kActHiLo>(W, n_tiles, kblocks, A, wg, epi, smem, xch, ticket);
+    }
+}
+
 // ---------------------------------------------------------------- epilogues
 // An epilogue sees every pair (column r, column r+8) of each finished tile:
 //   prefetch(t0, stride, nt)  before the contraction of a round (tiles t0 + stride*j, j < nt):
@@ -694,6 +777,10 @@ __device__ __forceinline__ void stage_embed(const DevModel& M, const float* __re
                                             int nwg) {
     const int k = P.k;
     const int ntiles = M.d / 16;
+    // counts of the stages that split a tile over two workgroups: each returns to 0 by itself; a pass still starts clean
+    if (wg == 0 && M.split_down)
+        for (int i = threadIdx.x; i < ntiles; i += kThreads)
+            __hip_atomic_store(M.xch_ticket + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // 128 items per tile (16 rows x 8 column pairs); 4 tiles per sweep of the 512 threads
     const int sub = threadIdx.x >> 7, mm = (threadIdx.x >> 3) & 15, r = threadIdx.x & 7;
     for (int t0 = wg * 4; t0 < ntiles; t0 += nwg * 4) {
@@ -778,7 +865,8 @@ template <class DT>
 __device__ __forceinline__ void stage_down(const DevModel& M, const DevLayer& Ly, const float* gain_next,
                                            const PassArgs& P, int wg, int nwg, float* smem) {
     EpiResidual<DT, 6> epi{M, gain_next, P.k, {}, {}, {}, {}};
-    gemm_stage<DT>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, nwg, epi, smem);
+    if (M.split_down) gemm_stage_split<DT>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, epi, smem, M.xch, M.xch_ticket);
+    else gemm_stage<DT>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, nwg, epi, smem);
 }
 
 template <class DT>
@@ -1361,7 +1449,7 @@ static hipError_t launch_pass_t(const DevModel& M, const DevLayer* Ls, const Pas
         AMUSD_LAUNCH_SEQ(3, k_attn_merge, merge_wgs, dim3(64), 0, l)
         AMUSD_LAUNCH(4, k_oproj, d_wgs, kSmemBytes, l, nogain)
         AMUSD_LAUNCH(5, k_gateup, gu_wgs, kSmemBytes, l, nogain)
-        AMUSD_LAUNCH(6, k_down, d_wgs, kSmemBytes, l, gain_next)
+        AMUSD_LAUNCH(6, k_down, (M.split_down ? 2 * d_wgs : d_wgs), kSmemBytes, l, gain_next)
     }
     AMUSD_LAUNCH(7, k_lmhead, M.lm_wgs, kSmemBytes, 0, nogain)
 #undef AMUSD_LAUNCH_SEQ

@@ -59,6 +59,9 @@ SHAPES = {
     "tiny_gqa128_bf16": ModelShape("tiny_gqa128_bf16", 2, 512, 4, 1, 128, 1024, 2048, "bf16", 500000.0, seed=8),
     # one kv head shared by eight query heads (the largest group the attention stage supports), bf16
     "tiny_g8_bf16": ModelShape("tiny_g8_bf16", 2, 256, 8, 1, 64, 512, 2048, "bf16", 500000.0, seed=10),
+    # wide feed-forward layers on a narrow model: the down projection has few tiles and a long contraction
+    "tiny_wide_bf16": ModelShape("tiny_wide_bf16", 2, 256, 4, 2, 64, 4096, 2048, "bf16", 500000.0, seed=11),
+    "tiny_wide_fp32": ModelShape("tiny_wide_fp32", 2, 128, 2, 2, 64, 4096, 2048, "fp32", 10000.0, seed=12),
     "tiny_gqa_fp32": ModelShape("tiny_gqa_fp32", 2, 256, 8, 2, 32 * 2, 512, 2048, "fp32", 500000.0, seed=9),
     # 1B shape (draft model shape; also a verify workload of its own)
     "1b": ModelShape("1b", 16, 2048, 32, 8, 64, 8192, 32000, "bf16", 500000.0, seed=1),
