@@ -11,6 +11,8 @@ constexpr int kWaves = 8;          // waves per workgroup
 constexpr int kThreads = kWaves * 64;
 constexpr int kMaxTilesPerRound = 8;
 
+constexpr int kSplitTickets = 512; // pairs of workgroups that can share tiles in one stage (compute units / 2 at most)
+
 constexpr int kMaxSegs = kRows;    // a pass serves at most one sequence per row
 
 // One sequence's share of a pass: rows row0 .. row0+k-1 of the tile are its
@@ -73,7 +75,7 @@ struct DevModel {
     int bpw;              // key blocks a wave walks in one attention work unit
     int max_chunks;
     int lm_wgs;           // workgroups that produce arg-max partials
-    int split_down;       // 1: the down projection's tiles are shared by two workgroups each (K halves)
+    int split_down;       // tiles per pair of workgroups that share their K range in the down projection (0: no sharing)
     float eps, att_scale;
     const DevLayer* layers;
     const void* embed;    // [V][d] storage dtype, row-major
@@ -87,8 +89,9 @@ struct DevModel {
     void* Q_hi;           // [16][qdim]
     void* Q_lo;
     float* att_part;      // [units][G][16][hd+4]: numerator[hd], max, denominator, 2 pad; units <= n_slots*Hkv*max_chunks
-    float* xch;           // [d/16 tiles][2 K halves][16 rows][16 columns]: partial tiles of a stage split over workgroup pairs
-    int* xch_ticket;      // [d/16]: halves of the tile finished so far
+    float* xch;           // [group of tiles][2 K halves][tile of the group][16 rows][16 columns]: partial tiles of a stage
+                          // whose workgroups share K ranges in pairs (sized for the stage with most tiles)
+    int* xch_ticket;      // [kSplitTickets]: workgroups of the pair that have delivered their partials
     void* O;              // merged attention output, operand order, qdim columns
     void* H;              // SwiGLU output, operand order, F columns
     float* logits;        // [16][V]

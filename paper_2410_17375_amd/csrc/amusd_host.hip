@@ -375,9 +375,14 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
     D.max_chunks = D.ctx_pad / D.chunk;
     D.eps = c.rms_eps;
     D.att_scale = 1.0f / std::sqrt((float)c.head_dim);
-    {   // down projection: tiles for at most half the compute units and a long contraction -> two workgroups per tile
-        const int tiles = c.d_model / 16, kblocks = c.d_ffn / m->kb();
-        D.split_down = 2 * tiles <= m->nwg && kblocks % 2 == 0 && kblocks / kWaves >= 16 ? 1 : 0;
+    {   // Down projection: pairs of workgroups share K ranges when the contraction is long enough to pay for the
+        // hand-over: a tile per pair (tiles for at most half the compute units: every compute unit gets work) or
+        // two tiles per pair (a tile per compute unit: half the activation bytes per weight byte).  The same
+        // scheme on the QKV projection (three tiles per pair at the 8B shape instead of two or one tile per
+        // workgroup) measured no faster and is not built in.
+        const int tiles = c.d_model / 16, kblocks = c.d_ffn / m->kb(), pairs = m->nwg / 2;
+        const bool long_k = kblocks % 2 == 0 && kblocks / kWaves >= 16;
+        D.split_down = !long_k || pairs > kSplitTickets ? 0 : 2 * tiles <= m->nwg ? 1 : tiles == m->nwg ? 2 : 0;
     }
     const int lm_tiles = c.vocab / 16;
     D.lm_wgs = lm_tiles < m->nwg ? lm_tiles : m->nwg;
@@ -417,8 +422,9 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
     const size_t pass_seqs = D.n_slots < kMaxSegs ? D.n_slots : kMaxSegs;
     const size_t att_part_bytes = pass_seqs * D.Hkv * D.max_chunks * D.G * kRows * (D.hd + 4) * 4;
     ALLOC(D.att_part, float*, att_part_bytes, true)
-    ALLOC(D.xch, float*, (d / 16) * 2 * 256 * 4, true)
-    ALLOC(D.xch_ticket, int*, (d / 16) * 4, true)
+    const size_t xch_bytes = (size_t)D.d / 16 * 2 * 256 * 4;
+    ALLOC(D.xch, float*, xch_bytes, true)
+    ALLOC(D.xch_ticket, int*, kSplitTickets * 4, true)
     ALLOC(D.O, void*, kRows * q * 4, true)
     ALLOC(D.H, void*, kRows * F * 4, true)
     ALLOC(D.logits, float*, kRows * V * 4, true)
@@ -480,8 +486,8 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
         S.Q_hi = place(kRows * q * 4);
         S.Q_lo = place(kRows * q * 4);
         S.att_part = static_cast<float*>(place(att_part_bytes));
-        S.xch = static_cast<float*>(place((d / 16) * 2 * 256 * 4));
-        S.xch_ticket = static_cast<int*>(place((d / 16) * 4));
+        S.xch = static_cast<float*>(place(xch_bytes));
+        S.xch_ticket = static_cast<int*>(place(kSplitTickets * 4));
         S.O = place(kRows * q * 4);
         S.H = place(kRows * F * 4);
         S.best_val = static_cast<float*>(place((size_t)m->nwg * kRows * 4));

@@ -459,75 +459,84 @@ __device__ __forceinline__ float load_shared_f(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// A stage with at most half as many tiles as there are compute units and a long contraction (the down projection
-// of a narrow model) leaves half the chip without work, and what a compute unit can pull through its load path
-// then bounds the stage.  Here two workgroups share a tile: workgroup `tile` contracts over the lower half of the
-// K blocks, workgroup `n_tiles + tile` over the upper half.  Each writes its partial tile to device memory and
-// counts itself; whichever counts second adds the other's partial to its own (a + b, the same bits whoever is
-// second) and runs the epilogue.  Nobody waits for anybody.  kblocks is even (the host checks).
-template <class DT, int MODE, class Epi>
-__device__ __forceinline__ void gemm_stage_split_m(const uint4* __restrict__ W, int n_tiles, int kblocks,
+// Two workgroups share the work on NT tiles, each contracting over one half of the K blocks: workgroup g of the
+// first half of the grid takes the lower K half of tiles g, g + G, .. (G groups of NT tiles), workgroup G + g the
+// upper half.  Each writes its partial tiles to device memory and counts itself; whichever counts second adds the
+// other's partials to its own (a + b, the same bits whoever is second) and runs the epilogue.  Nobody waits for
+// anybody.  kblocks is even (the host checks).
+//   NT = 1: a stage with tiles for at most half the compute units and a long contraction (the down projection of a
+//           narrow model) leaves half the chip without work, and what one compute unit can pull through its load
+//           path then bounds the stage; the split puts every compute unit to work.
+//   NT = 2: a stage with one tile per compute unit moves as many activation bytes as weight bytes through each
+//           compute unit's load path; two tiles over half the K range need half the activation bytes per weight byte.
+template <class DT, int MODE, int NT, class Epi>
+__device__ __forceinline__ bool gemm_stage_split_m(const uint4* __restrict__ W, int n_tiles, int kblocks,
                                                    const void* __restrict__ A, int wg, Epi& epi, float* smem,
                                                    float* xch, int* ticket) {
     constexpr int SLOTS = kMaxTilesPerRound;
-    constexpr int D = MODE == kActHiLo ? 4 : 8;
+    constexpr int D = NT == 1 ? (MODE == kActHiLo ? 4 : 8) : 4;   // pipeline depth as in gemm_stage_m
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
-    const int tile = wg % n_tiles, half = wg / n_tiles;
+    const int groups = n_tiles / NT;                          // n_tiles is a multiple of NT (the host checks)
+    const int grp = wg % groups, half = wg / groups;
     const int kh = kblocks / 2;
     const KSlice ks = k_slice(kh, wg, wave, Epi::kStagger);
     const uint4* act = reinterpret_cast<const uint4*>(A);
-    epi.prefetch(tile, 0, 1);
+    epi.prefetch(grp, groups, NT);
     v4f acc[SLOTS];
 #pragma unroll
     for (int j = 0; j < SLOTS; ++j) acc[j] = v4f{0.f, 0.f, 0.f, 0.f};
-    if (ks.S > 0) gemm_accumulate<DT, MODE, 1, D>(acc, W, tile, 0, kblocks, ks.kb0 + half * kh, ks.S, ks.rot, act, lane);
-    if (MODE != kActPacked8 || m < 8) *reinterpret_cast<v4f*>(smem + (wave * SLOTS * 256 + m * 16 + g * 4)) = acc[0];
+    if (ks.S > 0) gemm_accumulate<DT, MODE, NT, D>(acc, W, grp, groups, kblocks, ks.kb0 + half * kh, ks.S, ks.rot, act, lane);
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+        if (MODE != kActPacked8 || m < 8) *reinterpret_cast<v4f*>(smem + ((wave * SLOTS + j) * 256 + m * 16 + g * 4)) = acc[j];
     epi.prepare();
     __syncthreads();
-    const int mm = (tid >> 3) & 15, r = tid & 7;
-    const bool valid = tid < 128 && (MODE != kActPacked8 || mm < 8);
+    const int j = tid >> 7, mm = (tid >> 3) & 15, r = tid & 7;             // thread -> (tile of the group, row, column pair)
+    const bool valid = j < NT && (MODE != kActPacked8 || mm < 8);
     float v1 = 0.f, v2 = 0.f;
     if (valid) {
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
-            v1 += smem[w * SLOTS * 256 + mm * 16 + r];
-            v2 += smem[w * SLOTS * 256 + mm * 16 + r + 8];
+            v1 += smem[(w * SLOTS + j) * 256 + mm * 16 + r];
+            v2 += smem[(w * SLOTS + j) * 256 + mm * 16 + r + 8];
         }
-        float* mine = xch + ((size_t)tile * 2 + half) * 256;
+        float* mine = xch + (((size_t)grp * 2 + half) * NT + j) * 256;
         store_shared_f(mine + mm * 16 + r, v1);
         store_shared_f(mine + mm * 16 + r + 8, v2);
     }
-    // the partial is complete in device memory once every wave's stores have been acknowledged; then it is counted
+    // the partials are complete in device memory once every wave's stores have been acknowledged; then they are counted
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     int* s_flag = reinterpret_cast<int*>(smem + kOffTileBestI);
     if (tid == 0) {
-        const int seen = __hip_atomic_fetch_add(ticket + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (seen == 1) __hip_atomic_store(ticket + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next layer
+        const int seen = __hip_atomic_fetch_add(ticket + grp, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (seen == 1) __hip_atomic_store(ticket + grp, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next layer
         *s_flag = seen == 1;
     }
     __syncthreads();
-    if (!*s_flag) return;                     // the other workgroup of the pair finishes the tile
+    if (!*s_flag) return false;               // the other workgroup of the pair finishes the tiles
     if (valid) {
-        const float* other = xch + ((size_t)tile * 2 + (1 - half)) * 256;
+        const float* other = xch + (((size_t)grp * 2 + (1 - half)) * NT + j) * 256;
         v1 += load_shared_f(other + mm * 16 + r);
         v2 += load_shared_f(other + mm * 16 + r + 8);
     }
-    epi.item(tile, 0, 0, mm, r, v1, v2, valid);
+    epi.item(grp + groups * (valid ? j : 0), j, 0, mm, r, v1, v2, valid);
     __syncthreads();
-    epi.round_end(1);
+    epi.round_end(NT);
+    return true;
 }
 
-template <class DT, class Epi>
-__device__ __forceinline__ void gemm_stage_split(const uint4* __restrict__ W, int n_tiles, int kblocks,
+// Returns true in the workgroup that finished the tiles (ran the epilogue), false in the one that was first.
+template <class DT, int NT, class Epi>
+__device__ __forceinline__ bool gemm_stage_split(const uint4* __restrict__ W, int n_tiles, int kblocks,
                                                  const void* __restrict__ A, int k_rows, int wg, Epi& epi, float* smem,
                                                  float* xch, int* ticket) {
     if constexpr (!DT::HAS_LO) {
-        gemm_stage_split_m<DT, kActSingle>(W, n_tiles, kblocks, A, wg, epi, smem, xch, ticket);
+        return gemm_stage_split_m<DT, kActSingle, NT>(W, n_tiles, kblocks, A, wg, epi, smem, xch, ticket);
     } else {
-        if (k_rows <= 8) gemm_stage_split_m<DT, kActPacked8>(W, n_tiles, kblocks, A, wg, epi, smem, xch, ticket);
-        else gemm_stage_split_m<DT, kActHiLo>(W, n_tiles, kblocks, A, wg, epi, smem, xch, ticket);
+        if (k_rows <= 8) return gemm_stage_split_m<DT, kActPacked8, NT>(W, n_tiles, kblocks, A, wg, epi, smem, xch, ticket);
+        return gemm_stage_split_m<DT, kActHiLo, NT>(W, n_tiles, kblocks, A, wg, epi, smem, xch, ticket);
     }
 }
 
@@ -779,7 +788,7 @@ __device__ __forceinline__ void stage_embed(const DevModel& M, const float* __re
     const int ntiles = M.d / 16;
     // counts of the stages that split a tile over two workgroups: each returns to 0 by itself; a pass still starts clean
     if (wg == 0 && M.split_down)
-        for (int i = threadIdx.x; i < ntiles; i += kThreads)
+        for (int i = threadIdx.x; i < kSplitTickets; i += kThreads)
             __hip_atomic_store(M.xch_ticket + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // 128 items per tile (16 rows x 8 column pairs); 4 tiles per sweep of the 512 threads
     const int sub = threadIdx.x >> 7, mm = (threadIdx.x >> 3) & 15, r = threadIdx.x & 7;
@@ -803,45 +812,52 @@ __device__ __forceinline__ void stage_embed(const DevModel& M, const float* __re
     }
 }
 
+// Cache rows of the kv heads whose attention units run on this workgroup's XCD, fetched into that XCD's L2 for
+// the attention stage, which is next and waits on exactly those loads (the units of kv head h run on XCD h mod
+// 8, and so does every workgroup with that index mod 8).  The calling workgroup is the rank-th of `count`
+// workgroups of its XCD that share the job.  Only whole key blocks below the first position this pass writes are
+// touched (one word per 128-byte line, delivered to LDS words nobody reads), so no line is fetched that this
+// kernel may still change; and only as long as those rows are a small part of an XCD's L2 (they are read once;
+// the O-projection's weights, fetched by the attention stage, need the rest of it).
+template <class DT>
+__device__ __forceinline__ void prefetch_cache_rows(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int rank,
+                                                    int count, float* smem) {
+    const size_t per_xcd = (size_t)(M.Hkv >> 3) * 2 * P.L0 * M.hd * DT::ESZ;
+    if (!kKvPrefetch || (M.Hkv & 7) != 0 || per_xcd > kKvPrefetchMax) return;
+    const int x = wg & 7;
+    const int safe = P.L0 / DT::BLOCK_KEYS * DT::BLOCK_KEYS;  // positions in blocks this pass leaves alone
+    const int half = (int)((size_t)safe * M.hd * DT::ESZ / 128);   // lines of one head's keys (values alike)
+    const int total = (M.Hkv >> 3) * 2 * half;                // lines for this XCD's kv heads
+    const int share = (total + count - 1) / count;
+    const size_t head_bytes = (size_t)M.ctx_pad * M.hd * DT::ESZ;
+    const size_t slot_bytes = (size_t)P.slot0 * M.Hkv * head_bytes;
+    const int end = (rank + 1) * share < total ? (rank + 1) * share : total;
+    for (int line = rank * share + (int)threadIdx.x; line < end; line += kThreads) {
+        const int hi = line / (2 * half), within = line % (2 * half);
+        const char* base = reinterpret_cast<const char*>(within < half ? Ly.kcache : Ly.vcache);
+        const char* p = base + slot_bytes + (size_t)(x + 8 * hi) * head_bytes +
+                        (size_t)(within < half ? within : within - half) * 128;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
+                                         (__attribute__((address_space(3))) void*)(smem + kOffPfSink + (threadIdx.x >> 6) * 64),
+                                         4, 0, 0);
+    }
+    prefetch_retire();
+}
+
 template <class DT, bool ONE>
 __device__ __forceinline__ void stage_qkv(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int nwg,
                                           float* smem) {
     EpiQKV<DT, ONE> epi{M, Ly, smem + kOffRstd, P, P.k, {}, {}, {}, 0, 0};
     epi.begin();
-    gemm_stage<DT>(Ly.wqkv, M.nqkv / 16, M.d / DT::KB, M.A, P.k, wg, nwg, epi, smem);
-    // The workgroups that own one tile fewer than the others finish early.  They use the time to fetch the layer's
-    // cached keys and values into L2 for the attention stage, which is next and waits on exactly those loads:
-    // the attention units of kv head h run on XCD h mod 8, and so does every workgroup with that index mod 8.
-    // Only whole key blocks below the first position this pass writes are touched (one word per 128-byte line,
-    // delivered to LDS words nobody reads), so no line is fetched that this kernel may still change.
+    const int n_tiles = M.nqkv / 16;
+    gemm_stage<DT>(Ly.wqkv, n_tiles, M.d / DT::KB, M.A, P.k, wg, nwg, epi, smem);
+    // The workgroups that own one tile fewer than the others finish early and fetch cache rows meanwhile.
     if constexpr (ONE) {
-        const int n_tiles = M.nqkv / 16;
         const int rounds = (n_tiles + nwg - 1) / nwg;
         const int w0 = n_tiles - (rounds - 1) * nwg;              // first workgroup with one tile fewer
-        // as long as those rows are a small part of an XCD's L2 (they are read once; the O-projection's weights,
-        // fetched by the attention stage, need the rest of it)
-        const size_t per_xcd = (size_t)(M.Hkv >> 3) * 2 * P.L0 * M.hd * DT::ESZ;
-        if (kKvPrefetch && (M.Hkv & 7) == 0 && rounds > 1 && w0 < nwg && wg >= w0 && per_xcd <= kKvPrefetchMax) {
-            const int x = wg & 7;
-            const int first = w0 + ((x - w0) & 7);                    // first such workgroup of XCD x
-            const int rank = (wg - first) >> 3, count = (nwg - first + 7) >> 3;
-            const int safe = P.L0 / DT::BLOCK_KEYS * DT::BLOCK_KEYS;  // positions in blocks this pass leaves alone
-            const int half = (int)((size_t)safe * M.hd * DT::ESZ / 128);   // lines of one head's keys (values alike)
-            const int total = (M.Hkv >> 3) * 2 * half;                // lines for this XCD's kv heads
-            const int share = (total + count - 1) / count;
-            const size_t head_bytes = (size_t)M.ctx_pad * M.hd * DT::ESZ;
-            const size_t slot_bytes = (size_t)P.slot0 * M.Hkv * head_bytes;
-            const int end = (rank + 1) * share < total ? (rank + 1) * share : total;
-            for (int line = rank * share + (int)threadIdx.x; line < end; line += kThreads) {
-                const int hi = line / (2 * half), within = line % (2 * half);
-                const char* base = reinterpret_cast<const char*>(within < half ? Ly.kcache : Ly.vcache);
-                const char* p = base + slot_bytes + (size_t)(x + 8 * hi) * head_bytes +
-                                (size_t)(within < half ? within : within - half) * 128;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
-                                                 (__attribute__((address_space(3))) void*)(smem + kOffPfSink + (threadIdx.x >> 6) * 64),
-                                                 4, 0, 0);
-            }
-            prefetch_retire();
+        if (rounds > 1 && w0 < nwg && wg >= w0) {
+            const int first = w0 + (((wg & 7) - w0) & 7);            // first such workgroup of this XCD
+            prefetch_cache_rows<DT>(M, Ly, P, wg, (wg - first) >> 3, (nwg - first + 7) >> 3, smem);
         }
     }
 }
@@ -865,7 +881,8 @@ template <class DT>
 __device__ __forceinline__ void stage_down(const DevModel& M, const DevLayer& Ly, const float* gain_next,
                                            const PassArgs& P, int wg, int nwg, float* smem) {
     EpiResidual<DT, 6> epi{M, gain_next, P.k, {}, {}, {}, {}};
-    if (M.split_down) gemm_stage_split<DT>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, epi, smem, M.xch, M.xch_ticket);
+    if (M.split_down == 1) gemm_stage_split<DT, 1>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, epi, smem, M.xch, M.xch_ticket);
+    else if (M.split_down == 2) gemm_stage_split<DT, 2>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, epi, smem, M.xch, M.xch_ticket);
     else gemm_stage<DT>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, nwg, epi, smem);
 }
 
@@ -1449,7 +1466,7 @@ static hipError_t launch_pass_t(const DevModel& M, const DevLayer* Ls, const Pas
         AMUSD_LAUNCH_SEQ(3, k_attn_merge, merge_wgs, dim3(64), 0, l)
         AMUSD_LAUNCH(4, k_oproj, d_wgs, kSmemBytes, l, nogain)
         AMUSD_LAUNCH(5, k_gateup, gu_wgs, kSmemBytes, l, nogain)
-        AMUSD_LAUNCH(6, k_down, (M.split_down ? 2 * d_wgs : d_wgs), kSmemBytes, l, gain_next)
+        AMUSD_LAUNCH(6, k_down, (M.split_down == 1 ? 2 * d_wgs : d_wgs), kSmemBytes, l, gain_next)
     }
     AMUSD_LAUNCH(7, k_lmhead, M.lm_wgs, kSmemBytes, 0, nogain)
 #undef AMUSD_LAUNCH_SEQ

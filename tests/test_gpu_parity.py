@@ -56,7 +56,7 @@ def _check_rows(shape, g, logits_ref, k, where):
 
 
 @pytest.mark.parametrize("name", ["tiny_verify", "tiny_draft", "tiny_gqa_fp32", "tiny_gqa_bf16", "tiny_gqa128_bf16",
-                                  "tiny_g8_bf16", "tiny_wide_bf16", "tiny_wide_fp32"])
+                                  "tiny_g8_bf16", "tiny_wide_bf16", "tiny_wide_fp32", "one_layer_8b_width_bf16"])
 def test_prefill_and_verify_rounds_match_oracle(name):
     shape, g, o = _pair(name, 320)
     V = shape.vocab
@@ -148,7 +148,7 @@ def test_long_cache_of_one_kv_head_reaches_every_merge_path():
 
 
 @pytest.mark.parametrize("name", ["tiny_verify", "tiny_gqa_bf16", "tiny_gqa128_bf16", "tiny_g8_bf16", "tiny_wide_bf16",
-                                  "tiny_wide_fp32"])
+                                  "tiny_wide_fp32", "one_layer_8b_width_bf16"])
 def test_k_row_pass_equals_k_single_row_passes_bitwise(name):
     """On the GPU itself a row's result must not depend on how many rows the pass has."""
     A, load_model = _gpu()

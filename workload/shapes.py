@@ -62,6 +62,9 @@ SHAPES = {
     # wide feed-forward layers on a narrow model: the down projection has few tiles and a long contraction
     "tiny_wide_bf16": ModelShape("tiny_wide_bf16", 2, 256, 4, 2, 64, 4096, 2048, "bf16", 500000.0, seed=11),
     "tiny_wide_fp32": ModelShape("tiny_wide_fp32", 2, 128, 2, 2, 64, 4096, 2048, "fp32", 10000.0, seed=12),
+    # one layer with the 8B shape's attention block and model width: its QKV and down projections have as many
+    # tiles per compute unit as the 8B shape's (the forms of those stages that depend on that count run), at test size
+    "one_layer_8b_width_bf16": ModelShape("one_layer_8b_width_bf16", 1, 4096, 32, 8, 128, 4096, 2048, "bf16", 500000.0, seed=13),
     "tiny_gqa_fp32": ModelShape("tiny_gqa_fp32", 2, 256, 8, 2, 32 * 2, 512, 2048, "fp32", 500000.0, seed=9),
     # 1B shape (draft model shape; also a verify workload of its own)
     "1b": ModelShape("1b", 16, 2048, 32, 8, 64, 8192, 32000, "bf16", 500000.0, seed=1),
