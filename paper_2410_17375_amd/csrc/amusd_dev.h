@@ -11,6 +11,7 @@ constexpr int kWaves = 8;          // waves per workgroup
 constexpr int kThreads = kWaves * 64;
 constexpr int kMaxTilesPerRound = 8;
 
+constexpr int kSplitWaysMax = 2;   // K ranges a stage's tiles can be split into across workgroups
 constexpr int kSplitTickets = 512; // pairs of workgroups that can share tiles in one stage (compute units / 2 at most)
 
 constexpr int kMaxSegs = kRows;    // a pass serves at most one sequence per row
@@ -89,7 +90,7 @@ struct DevModel {
     void* Q_hi;           // [16][qdim]
     void* Q_lo;
     float* att_part;      // [units][G][16][hd+4]: numerator[hd], max, denominator, 2 pad; units <= n_slots*Hkv*max_chunks
-    float* xch;           // [group of tiles][2 K halves][tile of the group][16 rows][16 columns]: partial tiles of a stage
+    float* xch;           // [group of tiles][K range][tile of the group][16 rows][16 columns]: partial tiles of a stage
                           // whose workgroups share K ranges in pairs (sized for the stage with most tiles)
     int* xch_ticket;      // [kSplitTickets]: workgroups of the pair that have delivered their partials
     void* O;              // merged attention output, operand order, qdim columns

@@ -422,7 +422,7 @@ int amusd_model_create(const amusd_config* cfg, void* hip_stream, amusd_model** 
     const size_t pass_seqs = D.n_slots < kMaxSegs ? D.n_slots : kMaxSegs;
     const size_t att_part_bytes = pass_seqs * D.Hkv * D.max_chunks * D.G * kRows * (D.hd + 4) * 4;
     ALLOC(D.att_part, float*, att_part_bytes, true)
-    const size_t xch_bytes = (size_t)D.d / 16 * 2 * 256 * 4;
+    const size_t xch_bytes = (size_t)D.d / 16 * kSplitWaysMax * 256 * 4;    // a partial tile per tile and K range
     ALLOC(D.xch, float*, xch_bytes, true)
     ALLOC(D.xch_ticket, int*, kSplitTickets * 4, true)
     ALLOC(D.O, void*, kRows * q * 4, true)

@@ -459,34 +459,37 @@ __device__ __forceinline__ float load_shared_f(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Two workgroups share the work on NT tiles, each contracting over one half of the K blocks: workgroup g of the
-// first half of the grid takes the lower K half of tiles g, g + G, .. (G groups of NT tiles), workgroup G + g the
-// upper half.  Each writes its partial tiles to device memory and counts itself; whichever counts second adds the
-// other's partials to its own (a + b, the same bits whoever is second) and runs the epilogue.  Nobody waits for
-// anybody.  kblocks is even (the host checks).
-//   NT = 1: a stage with tiles for at most half the compute units and a long contraction (the down projection of a
-//           narrow model) leaves half the chip without work, and what one compute unit can pull through its load
-//           path then bounds the stage; the split puts every compute unit to work.
-//   NT = 2: a stage with one tile per compute unit moves as many activation bytes as weight bytes through each
+// WAYS workgroups share the work on NT tiles, each contracting over one WAYS-th of the K blocks: with G groups of NT
+// tiles, workgroup p * G + g takes the p-th K range of tiles g, g + G, ...  Each writes its partial tiles to device
+// memory and counts itself; whichever counts last adds the partials in the order of the K ranges (its own from
+// registers, so the bits do not depend on who is last) and runs the epilogue.  Nobody waits for anybody.  kblocks is
+// a multiple of WAYS and n_tiles of NT (the host checks).
+//   NT = 1, WAYS = 2: a stage with tiles for at most half the compute units and a long contraction (the down
+//           projection of a narrow model) leaves half the chip without work, and what one compute unit can pull
+//           through its load path then bounds the stage; the split puts every compute unit to work.
+//   NT = WAYS = 2: a stage with one tile per compute unit moves as many activation bytes as weight bytes through each
 //           compute unit's load path; two tiles over half the K range need half the activation bytes per weight byte.
-template <class DT, int MODE, int NT, class Epi>
+//           (Four tiles over a quarter of the K range measured no faster than no split at all: the last of four
+//           workgroups to finish has three partials to wait for and add.)
+template <class DT, int MODE, int NT, int WAYS, class Epi>
 __device__ __forceinline__ bool gemm_stage_split_m(const uint4* __restrict__ W, int n_tiles, int kblocks,
                                                    const void* __restrict__ A, int wg, Epi& epi, float* smem,
                                                    float* xch, int* ticket) {
+    static_assert(WAYS <= kSplitWaysMax, "the exchange buffer holds kSplitWaysMax partial tiles per tile");
     constexpr int SLOTS = kMaxTilesPerRound;
-    constexpr int D = NT == 1 ? (MODE == kActHiLo ? 4 : 8) : 4;   // pipeline depth as in gemm_stage_m
+    constexpr int D = NT == 1 ? (MODE == kActHiLo ? 4 : 8) : NT >= 4 && MODE == kActHiLo ? 3 : 4;   // as in gemm_stage_m
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
-    const int groups = n_tiles / NT;                          // n_tiles is a multiple of NT (the host checks)
-    const int grp = wg % groups, half = wg / groups;
-    const int kh = kblocks / 2;
+    const int groups = n_tiles / NT;
+    const int grp = wg % groups, part = wg / groups;
+    const int kh = kblocks / WAYS;
     const KSlice ks = k_slice(kh, wg, wave, Epi::kStagger);
     const uint4* act = reinterpret_cast<const uint4*>(A);
     epi.prefetch(grp, groups, NT);
     v4f acc[SLOTS];
 #pragma unroll
     for (int j = 0; j < SLOTS; ++j) acc[j] = v4f{0.f, 0.f, 0.f, 0.f};
-    if (ks.S > 0) gemm_accumulate<DT, MODE, NT, D>(acc, W, grp, groups, kblocks, ks.kb0 + half * kh, ks.S, ks.rot, act, lane);
+    if (ks.S > 0) gemm_accumulate<DT, MODE, NT, D>(acc, W, grp, groups, kblocks, ks.kb0 + part * kh, ks.S, ks.rot, act, lane);
 #pragma unroll
     for (int j = 0; j < NT; ++j)
         if (MODE != kActPacked8 || m < 8) *reinterpret_cast<v4f*>(smem + ((wave * SLOTS + j) * 256 + m * 16 + g * 4)) = acc[j];
@@ -501,7 +504,7 @@ __device__ __forceinline__ bool gemm_stage_split_m(const uint4* __restrict__ W, 
             v1 += smem[(w * SLOTS + j) * 256 + mm * 16 + r];
             v2 += smem[(w * SLOTS + j) * 256 + mm * 16 + r + 8];
         }
-        float* mine = xch + (((size_t)grp * 2 + half) * NT + j) * 256;
+        float* mine = xch + (((size_t)grp * WAYS + part) * NT + j) * 256;
         store_shared_f(mine + mm * 16 + r, v1);
         store_shared_f(mine + mm * 16 + r + 8, v2);
     }
@@ -511,15 +514,27 @@ __device__ __forceinline__ bool gemm_stage_split_m(const uint4* __restrict__ W, 
     int* s_flag = reinterpret_cast<int*>(smem + kOffTileBestI);
     if (tid == 0) {
         const int seen = __hip_atomic_fetch_add(ticket + grp, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (seen == 1) __hip_atomic_store(ticket + grp, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next layer
-        *s_flag = seen == 1;
+        if (seen == WAYS - 1) __hip_atomic_store(ticket + grp, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next layer
+        *s_flag = seen == WAYS - 1;
     }
     __syncthreads();
-    if (!*s_flag) return false;               // the other workgroup of the pair finishes the tiles
+    if (!*s_flag) return false;               // another workgroup of the group finishes the tiles
     if (valid) {
-        const float* other = xch + (((size_t)grp * 2 + (1 - half)) * NT + j) * 256;
-        v1 += load_shared_f(other + mm * 16 + r);
-        v2 += load_shared_f(other + mm * 16 + r + 8);
+        float o1[WAYS], o2[WAYS];
+#pragma unroll
+        for (int p = 0; p < WAYS; ++p) {      // all loads first: one round trip
+            const float* other = xch + (((size_t)grp * WAYS + p) * NT + j) * 256;
+            o1[p] = load_shared_f(other + mm * 16 + r);
+            o2[p] = load_shared_f(other + mm * 16 + r + 8);
+        }
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int p = 0; p < WAYS; ++p) {      // K ranges in order; this workgroup's own partial from its registers
+            s1 += p == part ? v1 : o1[p];
+            s2 += p == part ? v2 : o2[p];
+        }
+        v1 = s1;
+        v2 = s2;
     }
     epi.item(grp + groups * (valid ? j : 0), j, 0, mm, r, v1, v2, valid);
     __syncthreads();
@@ -528,15 +543,15 @@ __device__ __forceinline__ bool gemm_stage_split_m(const uint4* __restrict__ W, 
 }
 
 // Returns true in the workgroup that finished the tiles (ran the epilogue), false in the one that was first.
-template <class DT, int NT, class Epi>
+template <class DT, int NT, int WAYS, class Epi>
 __device__ __forceinline__ bool gemm_stage_split(const uint4* __restrict__ W, int n_tiles, int kblocks,
                                                  const void* __restrict__ A, int k_rows, int wg, Epi& epi, float* smem,
                                                  float* xch, int* ticket) {
     if constexpr (!DT::HAS_LO) {
-        return gemm_stage_split_m<DT, kActSingle, NT>(W, n_tiles, kblocks, A, wg, epi, smem, xch, ticket);
+        return gemm_stage_split_m<DT, kActSingle, NT, WAYS>(W, n_tiles, kblocks, A, wg, epi, smem, xch, ticket);
     } else {
-        if (k_rows <= 8) return gemm_stage_split_m<DT, kActPacked8, NT>(W, n_tiles, kblocks, A, wg, epi, smem, xch, ticket);
-        return gemm_stage_split_m<DT, kActHiLo, NT>(W, n_tiles, kblocks, A, wg, epi, smem, xch, ticket);
+        if (k_rows <= 8) return gemm_stage_split_m<DT, kActPacked8, NT, WAYS>(W, n_tiles, kblocks, A, wg, epi, smem, xch, ticket);
+        return gemm_stage_split_m<DT, kActHiLo, NT, WAYS>(W, n_tiles, kblocks, A, wg, epi, smem, xch, ticket);
     }
 }
 
@@ -881,8 +896,8 @@ template <class DT>
 __device__ __forceinline__ void stage_down(const DevModel& M, const DevLayer& Ly, const float* gain_next,
                                            const PassArgs& P, int wg, int nwg, float* smem) {
     EpiResidual<DT, 6> epi{M, gain_next, P.k, {}, {}, {}, {}};
-    if (M.split_down == 1) gemm_stage_split<DT, 1>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, epi, smem, M.xch, M.xch_ticket);
-    else if (M.split_down == 2) gemm_stage_split<DT, 2>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, epi, smem, M.xch, M.xch_ticket);
+    if (M.split_down == 1) gemm_stage_split<DT, 1, 2>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, epi, smem, M.xch, M.xch_ticket);
+    else if (M.split_down == 2) gemm_stage_split<DT, 2, 2>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, epi, smem, M.xch, M.xch_ticket);
     else gemm_stage<DT>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, nwg, epi, smem);
 }
 
