@@ -17,8 +17,9 @@ re-extension == fresh recomputation; attention == brute-force float64 softmax;
 the whole decoder == an independently maintained Llama implementation
 (transformers' LlamaForCausalLM, float64) loaded with the same weights; RoPE,
 RMSNorm and SiLU closed forms; accept-length distribution closed form.
-The paper prints no token or logit values, so absolute logits are pinned only
-through those checks.
+The float32 route (stored 8B-shape values, timed baseline) is held against the
+float64 route at the 1B shape (16 layers, d = 2048).  The paper prints no token
+or logit values, so absolute logits are pinned only through those checks.
 """
 from .decoder import Decoder, rmsnorm, silu, rope_rotate, rope_cos_sin, attention_rows
 from .speculative import (verify_pass, VerifyResult, greedy_autoregressive,
