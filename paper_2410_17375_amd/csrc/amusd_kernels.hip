@@ -319,14 +319,14 @@ __device__ __forceinline__ void gemm_accumulate(v4f (&out)[kMaxTilesPerRound], c
 struct KSlice {
     int kb0, S, rot;
 };
-__device__ __forceinline__ KSlice k_slice(int kblocks, int wg, int wave, bool stagger) {
+__device__ __forceinline__ KSlice k_slice(int kblocks, int wg, int wave, bool stagger, int rot_wg, int rot_wave) {
     const int simd = wave & 3, young = wave >> 2;
     const int q0 = (kblocks * simd) / 4, q1 = (kblocks * (simd + 1)) / 4;
     const int cut = q0 + ((q1 - q0) * kOldShare + 8) / 16;
     KSlice k;
     k.kb0 = young ? cut : q0;
     k.S = (young ? q1 : cut) - k.kb0;
-    k.rot = stagger && k.S > 0 ? (int)(((unsigned)wg * 5u + (unsigned)wave * 11u) % (unsigned)k.S) : 0;
+    k.rot = stagger && k.S > 0 ? (int)(((unsigned)wg * (unsigned)rot_wg + (unsigned)wave * (unsigned)rot_wave) % (unsigned)k.S) : 0;
     return k;
 }
 __device__ __forceinline__ int round_tiles(int left) { return left >= 8 ? 8 : left == 7 ? 7 : left >= 4 ? 4 : left >= 2 ? 2 : 1; }
@@ -342,6 +342,7 @@ struct NextWeights {
     const uint4* W;
     int n_tiles, kblocks;
     bool stagger;
+    int rot_wg, rot_wave;   // the consumer's K-walk coefficients (k_slice)
 };
 // Fragments [F0, F1) of consumer wave `cwave`, counted in the order the consumer's pipeline asks for them
 // (stage-major over the tiles of its first round); 8 fragments (8 KiB) per load instruction of the calling wave.
@@ -349,7 +350,7 @@ struct NextWeights {
 template <int F0, int F1>
 __device__ __forceinline__ void prefetch_frags(const NextWeights& nx, int wg, int nwg, int cwave, int lane, float* lds_sink) {
     if (F1 <= F0 || wg >= nx.n_tiles) return;
-    const KSlice ks = k_slice(nx.kblocks, wg, cwave, nx.stagger);
+    const KSlice ks = k_slice(nx.kblocks, wg, cwave, nx.stagger, nx.rot_wg, nx.rot_wave);
     if (ks.S <= 0) return;
     const int nt = round_tiles((nx.n_tiles - wg + nwg - 1) / nwg);
 #pragma unroll
@@ -374,7 +375,7 @@ __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_
     constexpr int SLOTS = kMaxTilesPerRound;                  // partial tiles per wave per round
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
-    const KSlice ks = k_slice(kblocks, wg, wave, Epi::kStagger);
+    const KSlice ks = k_slice(kblocks, wg, wave, Epi::kStagger, Epi::kRotWg, Epi::kRotWave);
     const int kb0 = ks.kb0, S = ks.S, rot = ks.rot;
     const int mine = wg < n_tiles ? (n_tiles - wg + nwg - 1) / nwg : 0;
     const uint4* act = reinterpret_cast<const uint4*>(A);
@@ -483,7 +484,7 @@ __device__ __forceinline__ bool gemm_stage_split_m(const uint4* __restrict__ W, 
     const int groups = n_tiles / NT;
     const int grp = wg % groups, part = wg / groups;
     const int kh = kblocks / WAYS;
-    const KSlice ks = k_slice(kh, wg, wave, Epi::kStagger);
+    const KSlice ks = k_slice(kh, wg, wave, Epi::kStagger, Epi::kRotWg, Epi::kRotWave);
     const uint4* act = reinterpret_cast<const uint4*>(A);
     epi.prefetch(grp, groups, NT);
     v4f acc[SLOTS];
@@ -595,6 +596,9 @@ template <class DT, int STAGE>
 struct EpiResidual {   // O-projection and down-projection: X += C, feed the next norm
     static constexpr int kStage = STAGE;
     static constexpr bool kStagger = true;
+    // Where a wave starts its K walk (k_slice), swept per stage on the chip: the down projection is fastest when
+    // all workgroups start alike and only the waves differ, the O-projection when nobody is shifted by its wave.
+    static constexpr int kRotWg = STAGE == 6 ? 0 : 5, kRotWave = STAGE == 6 ? 3 : 0;
     const DevModel& M;
     const float* gain_next;
     int k_rows;
@@ -628,6 +632,7 @@ template <class DT, bool ONE>
 struct EpiQKV {
     static constexpr int kStage = 1;        // RMS scale, rotary embedding on (i, i+hd/2) pairs, Q to its buffer, K/V appended to the cache
     static constexpr bool kStagger = false; // measured slower with staggered K walks (short slices, two tile counts)
+    static constexpr int kRotWg = 0, kRotWave = 0;
     const DevModel& M;
     const DevLayer& Ly;
     float* rstd;         // LDS
@@ -730,6 +735,7 @@ template <class DT>
 struct EpiSwiGLU {     // tile rows 0-7 are gate features, 8-15 the matching up features
     static constexpr int kStage = 5;
     static constexpr bool kStagger = true;
+    static constexpr int kRotWg = 5, kRotWave = 11;   // an even wave coefficient costs 0.3-6 us per launch
     const DevModel& M;
     float* rstd;
     int k_rows;
@@ -751,6 +757,7 @@ __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { retur
 struct EpiLMHead {
     static constexpr int kStage = 7;     // logits (optionally stored); per-row arg-max over this workgroup's tiles, lowest id on ties
     static constexpr bool kStagger = true;
+    static constexpr int kRotWg = 5, kRotWave = 11;
     const DevModel& M;
     float* smem;
     int k_rows, keep;
@@ -952,7 +959,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
     // no attention unit (at short contexts there are fewer units than compute units).  Such a workgroup serves the
     // O-projection workgroups of its own XCD in turn with the other idle workgroups of that XCD.
     if (kAttPf > 0 && wg >= units) {
-        const NextWeights wo{Ly.wo, M.d / 16, M.qdim / DT::KB, true};
+        const NextWeights wo{Ly.wo, M.d / 16, M.qdim / DT::KB, true, EpiResidual<DT, 4>::kRotWg, EpiResidual<DT, 4>::kRotWave};
         const int consumers = wo.n_tiles < nwg ? wo.n_tiles : nwg;      // workgroups of the O-projection
         const int x = wg & 7;
         const int first = units + ((x - units) & 7);                    // first idle workgroup of XCD x
