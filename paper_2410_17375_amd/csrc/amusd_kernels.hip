@@ -240,7 +240,6 @@ constexpr int kAttPfMax = 3;      // O-projection workgroups served by one idle 
 constexpr int kAttPfSleep = 0;    // s_sleep units (64 clocks) before the fetch (0: at once; the units find their cache rows in L2)
 constexpr size_t kKvPrefetchMax = 2u << 20;   // cache bytes per XCD up to which they do (context 4096 at the 8B shape)
 constexpr bool kKvPrefetch = true; // QKV workgroups with time to spare fetch the cache rows the attention stage reads next
-constexpr int kOldShare = 8;      // sixteenths of a SIMD's K range given to its first wave
 
 template <class DT, int MODE, int NT, int D>
 __device__ __forceinline__ void gemm_accumulate(v4f (&out)[kMaxTilesPerRound], const uint4* __restrict__ W, int tile0,
@@ -315,18 +314,19 @@ __device__ __forceinline__ void gemm_accumulate(v4f (&out)[kMaxTilesPerRound], c
 
 // A wave's share of the K blocks of a GEMM stage, and where in it the wave starts its walk: blocks
 // kb0 + stride * ((i + rot) mod S), i = 0 .. S-1.
-// K split: SIMD s hosts waves s and s+4; they share the K quarter of their SIMD.  The first wave of a
-// SIMD wins the issue arbitration and streams faster, so it takes the larger share (kOldShare/16).
+// K split: SIMD s hosts waves s and s+4; they share the K quarter of their SIMD, the first of them taking
+// old_share sixteenths (the first wave of a SIMD wins the issue arbitration and streams faster, but which split is
+// fastest was measured per stage, and it also shifts where the second wave's stream starts).
 // Interleaved form: the waves take every eighth block instead (the two waves of a SIMD neighbouring ones), so that a
 // workgroup's eight streams move through the tile as one window of 8 KiB.
 struct KSlice {
     int kb0, S, rot, stride;
 };
 __device__ __forceinline__ KSlice k_slice(int kblocks, int wg, int wave, bool stagger, int rot_wg, int rot_wave,
-                                          bool interleave) {
+                                          bool interleave, int old_share) {
     const int simd = wave & 3, young = wave >> 2;
     const int q0 = (kblocks * simd) / 4, q1 = (kblocks * (simd + 1)) / 4;
-    const int cut = q0 + ((q1 - q0) * kOldShare + 8) / 16;
+    const int cut = q0 + ((q1 - q0) * old_share + 8) / 16;
     KSlice k;
     k.kb0 = young ? cut : q0;
     k.S = (young ? q1 : cut) - k.kb0;
@@ -354,6 +354,7 @@ struct NextWeights {
     bool stagger;
     int rot_wg, rot_wave;   // the consumer's K-walk coefficients (k_slice)
     bool interleave;
+    int old_share;
 };
 // Fragments [F0, F1) of consumer wave `cwave`, counted in the order the consumer's pipeline asks for them
 // (stage-major over the tiles of its first round); 8 fragments (8 KiB) per load instruction of the calling wave.
@@ -361,7 +362,7 @@ struct NextWeights {
 template <int F0, int F1>
 __device__ __forceinline__ void prefetch_frags(const NextWeights& nx, int wg, int nwg, int cwave, int lane, float* lds_sink) {
     if (F1 <= F0 || wg >= nx.n_tiles) return;
-    const KSlice ks = k_slice(nx.kblocks, wg, cwave, nx.stagger, nx.rot_wg, nx.rot_wave, nx.interleave);
+    const KSlice ks = k_slice(nx.kblocks, wg, cwave, nx.stagger, nx.rot_wg, nx.rot_wave, nx.interleave, nx.old_share);
     if (ks.S <= 0) return;
     const int nt = round_tiles((nx.n_tiles - wg + nwg - 1) / nwg);
 #pragma unroll
@@ -386,7 +387,7 @@ __device__ __forceinline__ void gemm_stage_m(const uint4* __restrict__ W, int n_
     constexpr int SLOTS = kMaxTilesPerRound;                  // partial tiles per wave per round
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
-    const KSlice ks = k_slice(kblocks, wg, wave, Epi::kStagger, Epi::kRotWg, Epi::kRotWave, Epi::kInterleave);
+    const KSlice ks = k_slice(kblocks, wg, wave, Epi::kStagger, Epi::kRotWg, Epi::kRotWave, Epi::kInterleave, Epi::kOldShare);
     const int kb0 = ks.kb0, S = ks.S, rot = ks.rot;
     const int mine = wg < n_tiles ? (n_tiles - wg + nwg - 1) / nwg : 0;
     const uint4* act = reinterpret_cast<const uint4*>(A);
@@ -495,7 +496,7 @@ __device__ __forceinline__ bool gemm_stage_split_m(const uint4* __restrict__ W, 
     const int groups = n_tiles / NT;
     const int grp = wg % groups, part = wg / groups;
     const int kh = kblocks / WAYS;
-    const KSlice ks = k_slice(kh, wg, wave, Epi::kStagger, Epi::kRotWg, Epi::kRotWave, Epi::kInterleave);
+    const KSlice ks = k_slice(kh, wg, wave, Epi::kStagger, Epi::kRotWg, Epi::kRotWave, Epi::kInterleave, Epi::kOldShare);
     const uint4* act = reinterpret_cast<const uint4*>(A);
     epi.prefetch(grp, groups, NT);
     v4f acc[SLOTS];
@@ -611,6 +612,7 @@ struct EpiResidual {   // O-projection and down-projection: X += C, feed the nex
     // all workgroups start alike and only the waves differ, the O-projection when nobody is shifted by its wave.
     static constexpr int kRotWg = STAGE == 6 ? 0 : 5, kRotWave = STAGE == 6 ? 5 : 0;
     static constexpr bool kInterleave = STAGE == 6;   // down projection: 0.4 us per launch faster; the other stages equal or slower
+    static constexpr int kOldShare = 8;
     const DevModel& M;
     const float* gain_next;
     int k_rows;
@@ -646,6 +648,7 @@ struct EpiQKV {
     static constexpr bool kStagger = false; // measured slower with staggered K walks (short slices, two tile counts)
     static constexpr int kRotWg = 0, kRotWave = 0;
     static constexpr bool kInterleave = false;
+    static constexpr int kOldShare = 6;     // 12 + 20 of a SIMD's 32 K blocks: 0.4 us per launch faster than 16 + 16 (10 likewise; 4, 12, odd values not)
     const DevModel& M;
     const DevLayer& Ly;
     float* rstd;         // LDS
@@ -750,6 +753,7 @@ struct EpiSwiGLU {     // tile rows 0-7 are gate features, 8-15 the matching up 
     static constexpr bool kStagger = true;
     static constexpr int kRotWg = 5, kRotWave = 11;   // an even wave coefficient costs 0.3-6 us per launch
     static constexpr bool kInterleave = false;
+    static constexpr int kOldShare = 8;
     const DevModel& M;
     float* rstd;
     int k_rows;
@@ -773,6 +777,7 @@ struct EpiLMHead {
     static constexpr bool kStagger = true;
     static constexpr int kRotWg = 5, kRotWave = 11;
     static constexpr bool kInterleave = false;
+    static constexpr int kOldShare = 8;
     const DevModel& M;
     float* smem;
     int k_rows, keep;
@@ -975,7 +980,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
     // O-projection workgroups of its own XCD in turn with the other idle workgroups of that XCD.
     if (kAttPf > 0 && wg >= units) {
         const NextWeights wo{Ly.wo, M.d / 16, M.qdim / DT::KB, true, EpiResidual<DT, 4>::kRotWg, EpiResidual<DT, 4>::kRotWave,
-                              EpiResidual<DT, 4>::kInterleave};
+                              EpiResidual<DT, 4>::kInterleave, EpiResidual<DT, 4>::kOldShare};
         const int consumers = wo.n_tiles < nwg ? wo.n_tiles : nwg;      // workgroups of the O-projection
         const int x = wg & 7;
         const int first = units + ((x - units) & 7);                    // first idle workgroup of XCD x
