@@ -159,11 +159,9 @@ __device__ __forceinline__ float wave_xor_add(float v, int off) { return v + __s
 // (so the fetch is the oldest entry of the load queue and never stalls the
 // weight stream) and reduced in a fixed order just before the epilogue.
 // Thread (row m = tid/32, slot s = tid%32) sums tiles s, s+32, ..; 512 threads.
-// LATE = true keeps the first use of the fetched values behind the contraction (an empty asm statement
-// stops the compiler from moving the loop-invariant sum in front of the round loop, where the wave would wait
-// for the values before it has asked for its first weights): 0.5 us per launch on the gate/up and LM-head
-// stages.  The QKV stage measured 0.2-2.8 us SLOWER that way and keeps the early use.
-template <bool LATE>
+// The first use of the fetched values stays behind the contraction: an empty asm statement stops the compiler from
+// moving the loop-invariant sum in front of the round loop, where the wave would wait for the values before it
+// has asked for its first weights (0.4-0.5 us per launch on each of the three stages that use it).
 struct RstdPrefetch {
     static constexpr int N = 8;      // covers d <= 4096 from registers; larger d loops in finish()
     float v[N];
@@ -174,7 +172,7 @@ struct RstdPrefetch {
         for (int t = 0; t < N; ++t) {
             const int idx = s + 32 * t;
             const float x = M.ssq[(idx < ntp ? idx : ntp - 1) * kRows + m];
-            v[t] = LATE || idx < ntp ? x : 0.f;
+            v[t] = x;
         }
     }
     __device__ __forceinline__ void finish(const DevModel& M, float* rstd) {
@@ -184,11 +182,8 @@ struct RstdPrefetch {
 #pragma unroll
         for (int t = 0; t < N; ++t) {
             float x = v[t];
-            if constexpr (LATE) {
-                asm volatile("" : "+v"(x));
-                x = s + 32 * t < ntp ? x : 0.f;
-            }
-            acc += x;
+            asm volatile("" : "+v"(x));
+            acc += s + 32 * t < ntp ? x : 0.f;
         }
         for (int idx = s + 32 * N; idx < ntp; idx += 32) acc += M.ssq[idx * kRows + m];
         acc = wave_xor_add(acc, 16);
@@ -654,7 +649,7 @@ struct EpiQKV {
     float* rstd;         // LDS
     const PassArgs& P;
     int k_rows;
-    RstdPrefetch<false> pre;
+    RstdPrefetch pre;
     float pc[2], ps[2];
     // Position and cache of this thread's row (both items of a thread belong to the same row).  The 16-bit form
     // keeps them in two registers from the start of the kernel (0.5 us per launch faster than looking them up where
@@ -757,7 +752,7 @@ struct EpiSwiGLU {     // tile rows 0-7 are gate features, 8-15 the matching up 
     const DevModel& M;
     float* rstd;
     int k_rows;
-    RstdPrefetch<true> pre;
+    RstdPrefetch pre;
     __device__ __forceinline__ void prefetch(int, int, int) {}
     __device__ __forceinline__ void prepare() { pre.finish(M, rstd); }
     __device__ __forceinline__ void item(int tile, int /*slot*/, int /*it*/, int mm, int r, float v1, float v2, bool valid) {
@@ -783,7 +778,7 @@ struct EpiLMHead {
     int k_rows, keep;
     float run_v;         // thread mm < 16 keeps the workgroup's running best for row mm
     int run_i;
-    RstdPrefetch<true> pre;
+    RstdPrefetch pre;
     __device__ __forceinline__ void prefetch(int, int, int) {}
     __device__ __forceinline__ void prepare() { pre.finish(M, smem + kOffRstd); }
     __device__ __forceinline__ void item(int tile, int slot, int /*it*/, int mm, int r, float v1, float v2, bool valid) {
