@@ -158,40 +158,58 @@ __device__ __forceinline__ float wave_xor_add(float v, int off) { return v + __s
 // The per-tile partial sums of squares are fetched at the start of a stage
 // (so the fetch is the oldest entry of the load queue and never stalls the
 // weight stream) and reduced in a fixed order just before the epilogue.
-// Thread (row m = tid/32, slot s = tid%32) sums tiles s, s+32, ..; 512 threads.
 // The first use of the fetched values stays behind the contraction: an empty asm statement stops the compiler from
 // moving the loop-invariant sum in front of the round loop, where the wave would wait for the values before it
 // has asked for its first weights (0.4-0.5 us per launch on each of the three stages that use it).
+// Only the first wave of each SIMD (waves 0-3) does this work, for the rows the pass has: those waves finish their
+// K share well before their SIMD's second wave, so the chain of dependent shuffles, the division and the root
+// (0.45 us) run while the others still stream, instead of after the last of them.
+// Thread (row m = tid/32 and m + 8, slot s = tid%32) of waves 0-3 sums tiles s, s+32, ..
 struct RstdPrefetch {
     static constexpr int N = 8;      // covers d <= 4096 from registers; larger d loops in finish()
-    float v[N];
-    __device__ __forceinline__ void begin(const DevModel& M) {
-        const int m = threadIdx.x >> 5, s = threadIdx.x & 31;
+    float v[2][N];
+    int k_rows;
+    __device__ __forceinline__ void begin(const DevModel& M, int rows) {
+        k_rows = rows;
+        if (threadIdx.x >= kThreads / 2) return;
+        const int s = threadIdx.x & 31;
         const int ntp = M.d / 16;
 #pragma unroll
-        for (int t = 0; t < N; ++t) {
-            const int idx = s + 32 * t;
-            const float x = M.ssq[(idx < ntp ? idx : ntp - 1) * kRows + m];
-            v[t] = x;
+        for (int h = 0; h < 2; ++h) {
+            const int m = (threadIdx.x >> 5) + 8 * h;
+            if (m < k_rows) {
+#pragma unroll
+                for (int t = 0; t < N; ++t) {
+                    const int idx = s + 32 * t;
+                    v[h][t] = M.ssq[(idx < ntp ? idx : ntp - 1) * kRows + m];
+                }
+            }
         }
     }
     __device__ __forceinline__ void finish(const DevModel& M, float* rstd) {
-        const int m = threadIdx.x >> 5, s = threadIdx.x & 31;
+        if (threadIdx.x >= kThreads / 2) return;
+        const int s = threadIdx.x & 31;
         const int ntp = M.d / 16;
-        float acc = 0.f;
 #pragma unroll
-        for (int t = 0; t < N; ++t) {
-            float x = v[t];
-            asm volatile("" : "+v"(x));
-            acc += s + 32 * t < ntp ? x : 0.f;
+        for (int h = 0; h < 2; ++h) {
+            const int m = (threadIdx.x >> 5) + 8 * h;
+            if (m < k_rows) {
+                float acc = 0.f;
+#pragma unroll
+                for (int t = 0; t < N; ++t) {
+                    float x = v[h][t];
+                    asm volatile("" : "+v"(x));
+                    acc += s + 32 * t < ntp ? x : 0.f;
+                }
+                for (int idx = s + 32 * N; idx < ntp; idx += 32) acc += M.ssq[idx * kRows + m];
+                acc = wave_xor_add(acc, 16);
+                acc = wave_xor_add(acc, 8);
+                acc = wave_xor_add(acc, 4);
+                acc = wave_xor_add(acc, 2);
+                acc = wave_xor_add(acc, 1);
+                if (s == 0) rstd[m] = 1.0f / sqrtf(acc / (float)M.d + M.eps);
+            }
         }
-        for (int idx = s + 32 * N; idx < ntp; idx += 32) acc += M.ssq[idx * kRows + m];
-        acc = wave_xor_add(acc, 16);
-        acc = wave_xor_add(acc, 8);
-        acc = wave_xor_add(acc, 4);
-        acc = wave_xor_add(acc, 2);
-        acc = wave_xor_add(acc, 1);
-        if (s == 0) rstd[m] = 1.0f / sqrtf(acc / (float)M.d + M.eps);
     }
 };
 
@@ -670,7 +688,7 @@ struct EpiQKV {
             pos_ = lookup_pos(mm);
             slot_ = lookup_slot(mm);
         }
-        pre.begin(M);
+        pre.begin(M, k_rows);
     }
     __device__ __forceinline__ int row_pos(int mm) const { return kKeepRow ? pos_ : lookup_pos(mm); }
     __device__ __forceinline__ int row_slot(int mm) const { return kKeepRow ? slot_ : lookup_slot(mm); }
@@ -884,6 +902,12 @@ __device__ __forceinline__ void prefetch_cache_rows(const DevModel& M, const Dev
 template <class DT, bool ONE>
 __device__ __forceinline__ void stage_qkv(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int nwg,
                                           float* smem) {
+    // All kernel arguments the stage needs in one batch at entry.  Left alone the compiler loads an argument where it
+    // is first used, and the stage waited for argument memory six times in a row before its first weight load.
+    pin_scalar(Ly.wqkv); pin_scalar(M.A); pin_scalar(M.ssq); pin_scalar(M.d); pin_scalar(M.nqkv); pin_scalar(P.k);
+    pin_scalar(M.hd); pin_scalar(M.qdim); pin_scalar(M.kvdim); pin_scalar(M.Hkv); pin_scalar(M.ctx_pad);
+    pin_scalar(M.rope_cos); pin_scalar(M.rope_sin); pin_scalar(M.Q_hi); pin_scalar(M.Q_lo); pin_scalar(M.eps);
+    pin_scalar(Ly.kcache); pin_scalar(Ly.vcache); pin_scalar(P.L0); pin_scalar(P.slot0);
     EpiQKV<DT, ONE> epi{M, Ly, smem + kOffRstd, P, P.k, {}, {}, {}, 0, 0};
     epi.begin();
     const int n_tiles = M.nqkv / 16;
@@ -902,6 +926,8 @@ __device__ __forceinline__ void stage_qkv(const DevModel& M, const DevLayer& Ly,
 template <class DT>
 __device__ __forceinline__ void stage_oproj(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int nwg,
                                             float* smem) {
+    pin_scalar(Ly.wo); pin_scalar(M.O); pin_scalar(M.d); pin_scalar(M.qdim); pin_scalar(P.k);   // one batch, as in stage_qkv
+    pin_scalar(M.X); pin_scalar(M.A); pin_scalar(M.ssq); pin_scalar(Ly.g_mlp);
     EpiResidual<DT, 4> epi{M, Ly.g_mlp, P.k, {}, {}, {}, {}};
     gemm_stage<DT>(Ly.wo, M.d / 16, M.qdim / DT::KB, M.O, P.k, wg, nwg, epi, smem);
 }
@@ -909,14 +935,18 @@ __device__ __forceinline__ void stage_oproj(const DevModel& M, const DevLayer& L
 template <class DT>
 __device__ __forceinline__ void stage_gateup(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int nwg,
                                              float* smem) {
+    pin_scalar(Ly.wgu); pin_scalar(M.A); pin_scalar(M.ssq); pin_scalar(M.d); pin_scalar(M.F); pin_scalar(P.k);   // one batch
+    pin_scalar(M.H); pin_scalar(M.eps);
     EpiSwiGLU<DT> epi{M, smem + kOffRstd, P.k, {}};
-    epi.pre.begin(M);
+    epi.pre.begin(M, P.k);
     gemm_stage<DT>(Ly.wgu, 2 * M.F / 16, M.d / DT::KB, M.A, P.k, wg, nwg, epi, smem);
 }
 
 template <class DT>
 __device__ __forceinline__ void stage_down(const DevModel& M, const DevLayer& Ly, const float* gain_next,
                                            const PassArgs& P, int wg, int nwg, float* smem) {
+    pin_scalar(Ly.wd); pin_scalar(M.H); pin_scalar(M.d); pin_scalar(M.F); pin_scalar(P.k); pin_scalar(M.split_down);   // one batch
+    pin_scalar(M.xch); pin_scalar(M.xch_ticket); pin_scalar(M.X); pin_scalar(M.A); pin_scalar(M.ssq); pin_scalar(gain_next);
     EpiResidual<DT, 6> epi{M, gain_next, P.k, {}, {}, {}, {}};
     if (M.split_down == 1) gemm_stage_split<DT, 1, 2>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, epi, smem, M.xch, M.xch_ticket);
     else if (M.split_down == 2) gemm_stage_split<DT, 2, 2>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, epi, smem, M.xch, M.xch_ticket);
@@ -925,8 +955,10 @@ __device__ __forceinline__ void stage_down(const DevModel& M, const DevLayer& Ly
 
 template <class DT>
 __device__ __forceinline__ void stage_lmhead(const DevModel& M, const PassArgs& P, int wg, int nwg, float* smem) {
+    pin_scalar(M.wlm); pin_scalar(M.A); pin_scalar(M.ssq); pin_scalar(M.d); pin_scalar(M.V); pin_scalar(P.k);   // one batch
+    pin_scalar(M.eps); pin_scalar(P.keep_logits); pin_scalar(M.logits); pin_scalar(M.lm_wgs); pin_scalar(M.best_val); pin_scalar(M.best_idx);
     EpiLMHead epi{M, smem, P.k, P.keep_logits, -INFINITY, 0x7fffffff, {}};
-    epi.pre.begin(M);
+    epi.pre.begin(M, P.k);
     gemm_stage<DT>(M.wlm, M.V / 16, M.d / DT::KB, M.A, P.k, wg, nwg, epi, smem);
     if (threadIdx.x < kRows && wg < M.lm_wgs) {
         M.best_val[wg * kRows + threadIdx.x] = epi.run_v;
