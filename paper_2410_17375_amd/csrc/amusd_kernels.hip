@@ -907,7 +907,7 @@ __device__ __forceinline__ void stage_qkv(const DevModel& M, const DevLayer& Ly,
     pin_scalar(Ly.wqkv); pin_scalar(M.A); pin_scalar(M.ssq); pin_scalar(M.d); pin_scalar(M.nqkv); pin_scalar(P.k);
     pin_scalar(M.hd); pin_scalar(M.qdim); pin_scalar(M.kvdim); pin_scalar(M.Hkv); pin_scalar(M.ctx_pad);
     pin_scalar(M.rope_cos); pin_scalar(M.rope_sin); pin_scalar(M.Q_hi); pin_scalar(M.Q_lo); pin_scalar(M.eps);
-    pin_scalar(Ly.kcache); pin_scalar(Ly.vcache); pin_scalar(P.L0); pin_scalar(P.slot0);
+    pin_scalar(Ly.kcache); pin_scalar(Ly.vcache); pin_scalar(P.L0); pin_scalar(P.slot0); pin_scalar(nwg);
     EpiQKV<DT, ONE> epi{M, Ly, smem + kOffRstd, P, P.k, {}, {}, {}, 0, 0};
     epi.begin();
     const int n_tiles = M.nqkv / 16;
@@ -927,7 +927,7 @@ template <class DT>
 __device__ __forceinline__ void stage_oproj(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int nwg,
                                             float* smem) {
     pin_scalar(Ly.wo); pin_scalar(M.O); pin_scalar(M.d); pin_scalar(M.qdim); pin_scalar(P.k);   // one batch, as in stage_qkv
-    pin_scalar(M.X); pin_scalar(M.A); pin_scalar(M.ssq); pin_scalar(Ly.g_mlp);
+    pin_scalar(M.X); pin_scalar(M.A); pin_scalar(M.ssq); pin_scalar(Ly.g_mlp); pin_scalar(nwg);
     EpiResidual<DT, 4> epi{M, Ly.g_mlp, P.k, {}, {}, {}, {}};
     gemm_stage<DT>(Ly.wo, M.d / 16, M.qdim / DT::KB, M.O, P.k, wg, nwg, epi, smem);
 }
@@ -936,7 +936,7 @@ template <class DT>
 __device__ __forceinline__ void stage_gateup(const DevModel& M, const DevLayer& Ly, const PassArgs& P, int wg, int nwg,
                                              float* smem) {
     pin_scalar(Ly.wgu); pin_scalar(M.A); pin_scalar(M.ssq); pin_scalar(M.d); pin_scalar(M.F); pin_scalar(P.k);   // one batch
-    pin_scalar(M.H); pin_scalar(M.eps);
+    pin_scalar(M.H); pin_scalar(M.eps); pin_scalar(nwg);
     EpiSwiGLU<DT> epi{M, smem + kOffRstd, P.k, {}};
     epi.pre.begin(M, P.k);
     gemm_stage<DT>(Ly.wgu, 2 * M.F / 16, M.d / DT::KB, M.A, P.k, wg, nwg, epi, smem);
@@ -946,7 +946,7 @@ template <class DT>
 __device__ __forceinline__ void stage_down(const DevModel& M, const DevLayer& Ly, const float* gain_next,
                                            const PassArgs& P, int wg, int nwg, float* smem) {
     pin_scalar(Ly.wd); pin_scalar(M.H); pin_scalar(M.d); pin_scalar(M.F); pin_scalar(P.k); pin_scalar(M.split_down);   // one batch
-    pin_scalar(M.xch); pin_scalar(M.xch_ticket); pin_scalar(M.X); pin_scalar(M.A); pin_scalar(M.ssq); pin_scalar(gain_next);
+    pin_scalar(M.xch); pin_scalar(M.xch_ticket); pin_scalar(M.X); pin_scalar(M.A); pin_scalar(M.ssq); pin_scalar(gain_next); pin_scalar(nwg);
     EpiResidual<DT, 6> epi{M, gain_next, P.k, {}, {}, {}, {}};
     if (M.split_down == 1) gemm_stage_split<DT, 1, 2>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, epi, smem, M.xch, M.xch_ticket);
     else if (M.split_down == 2) gemm_stage_split<DT, 2, 2>(Ly.wd, M.d / 16, M.F / DT::KB, M.H, P.k, wg, epi, smem, M.xch, M.xch_ticket);
@@ -956,7 +956,7 @@ __device__ __forceinline__ void stage_down(const DevModel& M, const DevLayer& Ly
 template <class DT>
 __device__ __forceinline__ void stage_lmhead(const DevModel& M, const PassArgs& P, int wg, int nwg, float* smem) {
     pin_scalar(M.wlm); pin_scalar(M.A); pin_scalar(M.ssq); pin_scalar(M.d); pin_scalar(M.V); pin_scalar(P.k);   // one batch
-    pin_scalar(M.eps); pin_scalar(P.keep_logits); pin_scalar(M.logits); pin_scalar(M.lm_wgs); pin_scalar(M.best_val); pin_scalar(M.best_idx);
+    pin_scalar(M.eps); pin_scalar(P.keep_logits); pin_scalar(M.logits); pin_scalar(M.lm_wgs); pin_scalar(M.best_val); pin_scalar(M.best_idx); pin_scalar(nwg);
     EpiLMHead epi{M, smem, P.k, P.keep_logits, -INFINITY, 0x7fffffff, {}};
     epi.pre.begin(M, P.k);
     gemm_stage<DT>(M.wlm, M.V / 16, M.d / DT::KB, M.A, P.k, wg, nwg, epi, smem);
@@ -987,7 +987,7 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
     pin_scalar(M.Q_hi); pin_scalar(M.Q_lo); pin_scalar(Ly.kcache); pin_scalar(Ly.vcache); pin_scalar(M.att_part);
     pin_scalar(Ly.wo); pin_scalar(M.d); pin_scalar(M.qdim); pin_scalar(M.Hkv); pin_scalar(M.ctx_pad);
     pin_scalar(M.att_scale); pin_scalar(M.G); pin_scalar(M.bpw); pin_scalar(P.L0); pin_scalar(P.k);
-    pin_scalar(P.nchunks0); pin_scalar(P.slot0); pin_scalar(P.units); pin_scalar(P.n_seg);
+    pin_scalar(P.nchunks0); pin_scalar(P.slot0); pin_scalar(P.units); pin_scalar(P.n_seg); pin_scalar(nwg);
     constexpr int FR = HD / 4 / DT::EPL;     // 16-byte fragments per lane along head_dim
     constexpr int HT = HD / 16;              // 16-wide head_dim tiles
     constexpr int BK = DT::BLOCK_KEYS, TPB = DT::TPB;
@@ -996,8 +996,9 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
     const int units = P.units;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
-    const int G = M.G, parts = kWaves / G, bpw = M.bpw;
-    const int hq = wave % G, part = wave / G;
+    const int G = M.G, bpw = M.bpw;
+    const int lg = __builtin_ctz((unsigned)G);         // G is 1, 2, 4 or 8 (checked at model creation): shifts, no divisions
+    const int parts = kWaves >> lg, hq = wave & (G - 1), part = wave >> lg;
     float* partO = smem;                               // [hq][part][16][HD + pad]
     float* partML = smem + kWaves * kRows * HDP;       // [hq][part][16][2]
     const int nblk = M.ctx_pad / BK;
@@ -1032,7 +1033,10 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
         // workgroups of one XCD (workgroup index mod 8 = kv head mod 8), and so do the merge waves of its query
         // heads: they then find the chunk partials in their own L2 instead of behind another XCD's write-back.
         int kvh, c;
-        if ((M.Hkv & 7) == 0) {
+        if (M.Hkv == 8) {                                // the usual case, without the divisions
+            kvh = ul & 7;
+            c = ul >> 3;
+        } else if ((M.Hkv & 7) == 0) {
             const int b = ul >> 3;
             kvh = (ul & 7) + 8 * (b / nchunks);
             c = b % nchunks;
@@ -1189,11 +1193,10 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
 template <class DT, int HD, bool ONE>
 __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassArgs& P, int wg, int nwg) {
     pin_scalar(M.att_part); pin_scalar(M.O); pin_scalar(M.Hq); pin_scalar(M.Hkv); pin_scalar(M.G); pin_scalar(M.chunk);
-    pin_scalar(P.k); pin_scalar(P.L0); pin_scalar(P.nchunks0);
+    pin_scalar(P.k); pin_scalar(P.L0); pin_scalar(P.nchunks0); pin_scalar(nwg);
     const int k = P.k, CS = M.chunk;
     const int lane = threadIdx.x & 63;
-    const int wpb = blockDim.x >> 6;
-    const int gw = wg * wpb + (threadIdx.x >> 6), nw = nwg * wpb;
+    const int gw = wg, nw = nwg;                      // launched with one wave per workgroup
     constexpr int PER = HD / 64, ROW = HD + kPartRow;
     for (int x = gw; x < M.Hq * k; x += nw) {
         int kvh, hq, mm;        // wave x -> (query head, row); same XCD as the attention units of the kv head
