@@ -152,7 +152,51 @@ __device__ __forceinline__ uint4 load_frag(const void* base, size_t elem_index) 
 template <class T>
 __device__ __forceinline__ void pin_scalar(const T& x) { asm volatile("" ::"s"(x)); }
 
-__device__ __forceinline__ float wave_xor_add(float v, int off) { return v + __shfl_xor(v, off, 64); }
+// The value that lane (l ^ OFF) holds, without going through the LDS crossbar (`__shfl_xor` compiles to
+// ds_bpermute, 50-100 clocks each, and these exchanges sit in chains on the critical path of every stage's end):
+// data-parallel-primitive modifiers inside a row of 16 lanes, the gfx950 row and half-wave swaps across rows.
+template <int OFF>
+__device__ __forceinline__ uint32_t lane_xor_u(uint32_t v) {
+    static_assert(OFF == 1 || OFF == 2 || OFF == 4 || OFF == 8 || OFF == 16 || OFF == 32, "one bit of the lane index");
+    const int x = (int)v;
+    if constexpr (OFF == 1) {
+        return (uint32_t)__builtin_amdgcn_update_dpp(x, x, 0xB1, 0xf, 0xf, false);        // quad_perm:[1,0,3,2]
+    } else if constexpr (OFF == 2) {
+        return (uint32_t)__builtin_amdgcn_update_dpp(x, x, 0x4E, 0xf, 0xf, false);        // quad_perm:[2,3,0,1]
+    } else if constexpr (OFF == 4) {
+        const int t = __builtin_amdgcn_update_dpp(x, x, 0x104, 0xf, 0x5, false);          // row_shl:4 into lanes 0-3, 8-11
+        return (uint32_t)__builtin_amdgcn_update_dpp(t, x, 0x114, 0xf, 0xa, false);       // row_shr:4 into lanes 4-7, 12-15
+    } else if constexpr (OFF == 8) {
+        return (uint32_t)__builtin_amdgcn_update_dpp(x, x, 0x128, 0xf, 0xf, false);       // row_ror:8
+    } else if constexpr (OFF == 16) {
+        const auto p = __builtin_amdgcn_permlane16_swap(v, v, false, false);   // p[0]: rows 0,0,2,2   p[1]: rows 1,1,3,3
+        return (threadIdx.x & 16) ? p[0] : p[1];
+    } else {
+        const auto p = __builtin_amdgcn_permlane32_swap(v, v, false, false);   // p[0]: lanes 0-31 twice   p[1]: lanes 32-63 twice
+        return (threadIdx.x & 32) ? p[0] : p[1];
+    }
+}
+template <int OFF>
+__device__ __forceinline__ float lane_xor(float v) { return __uint_as_float(lane_xor_u<OFF>(__float_as_uint(v))); }
+template <int OFF>
+__device__ __forceinline__ int lane_xor(int v) { return (int)lane_xor_u<OFF>((uint32_t)v); }
+template <int OFF>
+__device__ __forceinline__ float wave_xor_add(float v) { return v + lane_xor<OFF>(v); }
+// all 64 lanes, offsets 32, 16, .., 1 in that order
+__device__ __forceinline__ float wave_max_all(float v) {
+    v = fmaxf(v, lane_xor<32>(v)); v = fmaxf(v, lane_xor<16>(v)); v = fmaxf(v, lane_xor<8>(v));
+    v = fmaxf(v, lane_xor<4>(v)); v = fmaxf(v, lane_xor<2>(v)); v = fmaxf(v, lane_xor<1>(v));
+    return v;
+}
+__device__ __forceinline__ float wave_sum_all(float v) {
+    v = wave_xor_add<32>(v); v = wave_xor_add<16>(v); v = wave_xor_add<8>(v);
+    v = wave_xor_add<4>(v); v = wave_xor_add<2>(v); v = wave_xor_add<1>(v);
+    return v;
+}
+// lane j's value in every lane (j the same in all lanes)
+__device__ __forceinline__ float lane_value(float v, int j) {
+    return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(v), j));
+}
 
 // ---------------------------------------------------------------- RMS scale of the 16 rows
 // The per-tile partial sums of squares are fetched at the start of a stage
@@ -202,11 +246,11 @@ struct RstdPrefetch {
                     acc += s + 32 * t < ntp ? x : 0.f;
                 }
                 for (int idx = s + 32 * N; idx < ntp; idx += 32) acc += M.ssq[idx * kRows + m];
-                acc = wave_xor_add(acc, 16);
-                acc = wave_xor_add(acc, 8);
-                acc = wave_xor_add(acc, 4);
-                acc = wave_xor_add(acc, 2);
-                acc = wave_xor_add(acc, 1);
+                acc = wave_xor_add<16>(acc);
+                acc = wave_xor_add<8>(acc);
+                acc = wave_xor_add<4>(acc);
+                acc = wave_xor_add<2>(acc);
+                acc = wave_xor_add<1>(acc);
                 if (s == 0) rstd[m] = 1.0f / sqrtf(acc / (float)M.d + M.eps);
             }
         }
@@ -314,10 +358,10 @@ __device__ __forceinline__ void gemm_accumulate(v4f (&out)[kMaxTilesPerRound], c
             out[j] = acc[2 * j] + acc[2 * j + 1];
         } else if constexpr (MODE == kActPacked8) {
             v4f lo;
-            lo.x = __shfl_xor(acc[j].x, 8, 64);
-            lo.y = __shfl_xor(acc[j].y, 8, 64);
-            lo.z = __shfl_xor(acc[j].z, 8, 64);
-            lo.w = __shfl_xor(acc[j].w, 8, 64);
+            lo.x = lane_xor<8>(acc[j].x);
+            lo.y = lane_xor<8>(acc[j].y);
+            lo.z = lane_xor<8>(acc[j].z);
+            lo.w = lane_xor<8>(acc[j].w);
             out[j] = acc[j] + lo;
         } else {
             out[j] = acc[j];
@@ -611,9 +655,9 @@ __device__ __forceinline__ void residual_pair(const DevModel& M, float g1, float
         store_gemm_in<DT>(M.A, k_rows, mm, c2, x2 * g2);
         sq = x1 * x1 + x2 * x2;
     }
-    sq = wave_xor_add(sq, 1);
-    sq = wave_xor_add(sq, 2);
-    sq = wave_xor_add(sq, 4);
+    sq = wave_xor_add<1>(sq);
+    sq = wave_xor_add<2>(sq);
+    sq = wave_xor_add<4>(sq);
     if (on && r == 0) M.ssq[tile * kRows + mm] = sq;
 }
 
@@ -784,6 +828,13 @@ struct EpiSwiGLU {     // tile rows 0-7 are gate features, 8-15 the matching up 
 };
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
+// keeps the better of this lane's (value, index) and lane (l ^ OFF)'s
+template <int OFF>
+__device__ __forceinline__ void keep_better_xor(float& bv, int& bi) {
+    const float ov = lane_xor<OFF>(bv);
+    const int oi = lane_xor<OFF>(bi);
+    if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+}
 
 struct EpiLMHead {
     static constexpr int kStage = 7;     // logits (optionally stored); per-row arg-max over this workgroup's tiles, lowest id on ties
@@ -811,12 +862,9 @@ struct EpiLMHead {
         float bv = on ? z1 : -INFINITY;
         int bi = on ? c1 : 0x7fffffff;
         if (on && better(z2, c2, bv, bi)) { bv = z2; bi = c2; }
-#pragma unroll
-        for (int off = 1; off < 8; off <<= 1) {     // the 8 lanes of one (tile,row) are adjacent
-            const float ov = __shfl_xor(bv, off, 64);
-            const int oi = __shfl_xor(bi, off, 64);
-            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-        }
+        keep_better_xor<1>(bv, bi);                  // the 8 lanes of one (tile,row) are adjacent
+        keep_better_xor<2>(bv, bi);
+        keep_better_xor<4>(bv, bi);
         if (r == 0) {
             smem[kOffTileBestV + slot * kRows + mm] = bv;
             reinterpret_cast<int*>(smem)[kOffTileBestI + slot * kRows + mm] = bi;
@@ -1106,8 +1154,8 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
                     mx = fmaxf(mx, sv[t][e]);
                 }
             }
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            mx = fmaxf(mx, lane_xor<16>(mx));
+            mx = fmaxf(mx, lane_xor<32>(mx));
             const float mnew = fmaxf(mrun, mx);
             const float mref = mnew == -INFINITY ? 0.f : mnew;
             const float alpha = __expf(mrun - mref);     // 0 for the first visible block
@@ -1119,8 +1167,8 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
                     pv[t][e] = __expf(sv[t][e] - mref);
                     lsum += pv[t][e];
                 }
-            lsum = wave_xor_add(lsum, 16);
-            lsum = wave_xor_add(lsum, 32);
+            lsum = wave_xor_add<16>(lsum);
+            lsum = wave_xor_add<32>(lsum);
             lrun = lrun * alpha + lsum;
             mrun = mnew;
             uint4 ph, pl = zero4;
@@ -1240,14 +1288,12 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassAr
             const float mc = on ? p[HD] : -INFINITY;
             const float dc = on ? p[HD + 1] : 0.f;
             float Mg = mc;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) Mg = fmaxf(Mg, __shfl_xor(Mg, off, 64));
+            Mg = wave_max_all(Mg);
             const float Mnew = fmaxf(Mrun, Mg);       // finite: chunk 0 always holds key 0
             const float scale_old = __expf(Mrun - Mnew);
             const float wt = mc == -INFINITY ? 0.f : __expf(mc - Mnew);
             float dsum = wt * dc;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) dsum += __shfl_xor(dsum, off, 64);
+            dsum = wave_sum_all(dsum);
             den = den * scale_old + dsum;
 #pragma unroll
             for (int i = 0; i < PER; ++i) num[i] *= scale_old;
@@ -1255,13 +1301,13 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassAr
             if (c0 == 0) {
 #pragma unroll
                 for (int j = 0; j < CPRE; ++j) {
-                    const float wj = j < ng ? __shfl(wt, j, 64) : 0.f;
+                    const float wj = j < ng ? lane_value(wt, j) : 0.f;
 #pragma unroll
                     for (int i = 0; i < PER; ++i) num[i] += wj * pre[j][i];
                 }
             }
             for (int j = c0 == 0 ? CPRE : 0; j < ng; ++j) {
-                const float wj = __shfl(wt, j, 64);
+                const float wj = lane_value(wt, j);
                 const float* pj = base + (size_t)(c0 + j) * cstride;
 #pragma unroll
                 for (int i = 0; i < PER; ++i) num[i] += wj * pj[lane + 64 * i];
@@ -1291,12 +1337,12 @@ __device__ __forceinline__ void stage_accept(const DevModel& M, const PassArgs& 
                 const int i = M.best_idx[w * kRows + row];
                 if (better(v, i, bv, bi)) { bv = v; bi = i; }
             }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const float ov = __shfl_xor(bv, off, 64);
-            const int oi = __shfl_xor(bi, off, 64);
-            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-        }
+        keep_better_xor<32>(bv, bi);
+        keep_better_xor<16>(bv, bi);
+        keep_better_xor<8>(bv, bi);
+        keep_better_xor<4>(bv, bi);
+        keep_better_xor<2>(bv, bi);
+        keep_better_xor<1>(bv, bi);
         if (lane == 0) sg[row] = row < k ? bi : -1;
     }
     __syncthreads();
