@@ -1085,10 +1085,12 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
             kvh = ul & 7;
             c = ul >> 3;
         } else if ((M.Hkv & 7) == 0) {
+            asm volatile("");   // a real branch: no speculative divisions for the case above
             const int b = ul >> 3;
             kvh = (ul & 7) + 8 * (b / nchunks);
             c = b % nchunks;
         } else {
+            asm volatile("");
             kvh = ul / nchunks;
             c = ul % nchunks;
         }
@@ -1241,19 +1243,29 @@ __device__ __forceinline__ void stage_attention(const DevModel& M, const DevLaye
 template <class DT, int HD, bool ONE>
 __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassArgs& P, int wg, int nwg) {
     pin_scalar(M.att_part); pin_scalar(M.O); pin_scalar(M.Hq); pin_scalar(M.Hkv); pin_scalar(M.G); pin_scalar(M.chunk);
-    pin_scalar(P.k); pin_scalar(P.L0); pin_scalar(P.nchunks0); pin_scalar(nwg);
+    pin_scalar(P.k); pin_scalar(P.L0); pin_scalar(P.nchunks0);
+    (void)nwg;
     const int k = P.k, CS = M.chunk;
     const int lane = threadIdx.x & 63;
-    const int gw = wg, nw = nwg;                      // launched with one wave per workgroup
+    // launched with one wave per workgroup and one workgroup per (head, row): no loop, so that what only the
+    // rarer index forms below need (reciprocals for their divisions) is not computed ahead of it for all of them
     constexpr int PER = HD / 64, ROW = HD + kPartRow;
-    for (int x = gw; x < M.Hq * k; x += nw) {
+    const int x = wg;
+    if (x < M.Hq * k) {
         int kvh, hq, mm;        // wave x -> (query head, row); same XCD as the attention units of the kv head
-        if ((M.Hkv & 7) == 0) {
+        if (M.Hkv == 8) {       // the usual case without divisions: x = 8 (hq k + mm) + kvh, hq < G <= 8
+            const int y = x >> 3;
+            kvh = x & 7;
+            hq = (y >= k) + (y >= 2 * k) + (y >= 3 * k) + (y >= 4 * k) + (y >= 5 * k) + (y >= 6 * k) + (y >= 7 * k);
+            mm = y - hq * k;
+        } else if ((M.Hkv & 7) == 0) {
+            asm volatile("");   // a real branch: the divisions below are not to be computed speculatively for the case above
             const int y = x >> 3, per = M.G * k;
             kvh = (x & 7) + 8 * (y / per);
             hq = (y % per) / k;
             mm = y % k;
         } else {
+            asm volatile("");
             kvh = (x / k) / M.G;
             hq = (x / k) % M.G;
             mm = x % k;
@@ -1266,7 +1278,11 @@ __device__ __forceinline__ void stage_attn_merge(const DevModel& M, const PassAr
             nchunks = S.nchunks;
             pos = P.row_pos[mm];
         }
-        const int nch = pos / CS + 1;                 // chunks holding keys this row can see
+        // chunks holding keys this row can see: pos / CS + 1.  For a pass of one sequence without the division: its
+        // last row's count is nchunks, and a chunk has at least 16 keys, so the rows of a pass lie in at most two chunks
+        int nch;
+        if constexpr (ONE) nch = pos >= (nchunks - 1) * CS ? nchunks : nchunks - 1;
+        else nch = pos / CS + 1;
         const float* base = M.att_part + ((((size_t)unit0 + (size_t)kvh * nchunks) * M.G + hq) * kRows + mm) * ROW;
         const size_t cstride = (size_t)M.G * kRows * ROW;
         float Mrun = -INFINITY, den = 0.f, num[PER];
